@@ -1,0 +1,227 @@
+/*
+ * eesd.h - C ABI of the MI355X (gfx950) library for the hot path of
+ * Early-exiting Speculative Decoding (EESD).
+ *
+ * One context decodes one sequence (batch 1).  A decoding round is
+ *
+ *     eesd_draft_step x K  ->  eesd_verify  ->  eesd_accept  ->  eesd_rollback
+ *
+ * and eesd_generate runs the paper's whole loop (Algorithm 1) on top of those
+ * calls, with the draft length K of every round chosen on the host by the
+ * Beta-posterior Thompson-sampling controller (Section 3.3, Algorithm 2).
+ *
+ * Conventions that hold for every call:
+ *   - returns EESD_OK (0) or a negative eesd_status; never throws, never aborts;
+ *   - out-parameters are written only on success;
+ *   - "device" pointers are HIP device memory of the current device, "host"
+ *     pointers are ordinary host memory;
+ *   - all work is enqueued on the HIP stream given to eesd_create; calls that
+ *     return a value to the host synchronise that stream, the others do not;
+ *   - a context is not thread-safe.
+ *
+ * Model: a LLaMA-style pre-norm decoder (RMSNorm, rotary embedding on
+ * half-split pairs (j, j + head_dim/2), grouped-query causal attention,
+ * SwiGLU feed-forward).  The draft model of Section 3.1, Eq. 1 is the first
+ * n_draft_layers decoder layers of the target (same weights, same KV cache)
+ * followed by one extra decoder layer, an RMSNorm and an own LM head.
+ */
+#ifndef EESD_H
+#define EESD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct eesd_ctx eesd_ctx; /* opaque; created by eesd_create, freed by eesd_destroy */
+
+typedef enum eesd_status {
+    EESD_OK = 0,
+    EESD_EINVAL = -1,  /* null pointer, bad shape, token id outside [0, vocab) */
+    EESD_ENOMEM = -2,  /* device or host allocation failed */
+    EESD_ESTATE = -3,  /* call out of order (see the state machine below) */
+    EESD_ERANGE = -4,  /* sequence, draft count or schedule exceeds a configured limit */
+    EESD_EDEVICE = -5  /* a HIP call failed; eesd_last_error has the text */
+} eesd_status;
+
+enum { EESD_DTYPE_F32 = 0, EESD_DTYPE_BF16 = 1 };
+enum { EESD_TS_BETA = 0, EESD_TS_FIXED = 1, EESD_TS_SCHEDULE = 2 };
+enum { EESD_GEMM_AUTO = 0, EESD_GEMM_VALU = 1, EESD_GEMM_MFMA = 2 };
+
+typedef struct eesd_config {
+    int32_t n_layers;        /* L: decoder layers of the target model */
+    int32_t n_draft_layers;  /* N: leading layers the draft model shares with it (1 <= N < L) */
+    int32_t d_model;
+    int32_t n_heads;         /* query heads */
+    int32_t n_kv_heads;      /* key/value heads; n_heads % n_kv_heads == 0 */
+    int32_t head_dim;        /* even; 64 or 128 for the bf16 path */
+    int32_t d_ff;            /* SwiGLU width */
+    int32_t vocab;
+    float rms_eps;
+    float rope_base;
+    int32_t dtype;           /* EESD_DTYPE_*: storage type of the weights and of the KV cache;
+                                accumulation, residual stream, logits and probabilities are fp32 */
+    int32_t max_seq;         /* most tokens the KV cache can hold */
+    int32_t kv_page;         /* tokens per KV page (power of two, >= 16) */
+    int32_t k_cap;           /* most draft tokens per round, 1..15 */
+    float temperature;       /* 0 => greedy (Section 4.1 footnote); > 0 => sampling at that temperature */
+    uint64_t seed;           /* seed of the counter-based uniforms (draft, accept, resample, controller) */
+    double ts_alpha0;        /* prior Beta(alpha0, beta0) of the controller (Algorithm 2, step 1) */
+    double ts_beta0;
+    int32_t ts_mode;         /* EESD_TS_BETA: Algorithm 2; EESD_TS_FIXED: always k_cap drafts
+                                (the "w/o TS" ablation); EESD_TS_SCHEDULE: eesd_set_draft_schedule */
+    int32_t ts_update;       /* reading of Eq. 3-4: 0: r = a, n = min(a+1, K) (drafts the target judged);
+                                1: |Q_v| = a+1 taken literally, r = a, n = min(a+2, K) */
+    int32_t gemm_path;       /* EESD_GEMM_*: AUTO picks per pass; the others force one kernel family */
+    int32_t reserved;
+} eesd_config;
+
+/* One decoder layer.  Every matrix is row-major [out][in] in the configured dtype. */
+typedef struct eesd_layer_weights {
+    const void* attn_norm;  /* [d_model] */
+    const void* wqkv;       /* [(n_heads + 2 n_kv_heads) head_dim][d_model]: q heads, k heads, v heads */
+    const void* wo;         /* [d_model][n_heads head_dim] */
+    const void* ffn_norm;   /* [d_model] */
+    const void* w_gate_up;  /* [2 d_ff][d_model]: gate rows, then up rows */
+    const void* w_down;     /* [d_model][d_ff] */
+} eesd_layer_weights;
+
+/* DEVICE pointers, BORROWED: the caller owns the memory and keeps it alive and
+ * unchanged until eesd_destroy.  `layers` itself is a host array of n_layers entries
+ * (copied by eesd_create). */
+typedef struct eesd_weights {
+    const void* tok_emb;                /* [vocab][d_model] */
+    const eesd_layer_weights* layers;   /* host array, n_layers entries */
+    const void* final_norm;             /* [d_model] */
+    const void* lm_head;                /* [vocab][d_model], target head */
+    eesd_layer_weights ee_layer;        /* the early-exit decoder layer (Eq. 1, Transformer^e) */
+    const void* ee_norm;                /* [d_model] */
+    const void* ee_head;                /* [vocab][d_model], draft head W of Eq. 1 */
+} eesd_weights;
+
+/* Counters of Section 4.1 "Metrics" / Appendix D and the time buckets of the
+ * paper's breakdown table (drafting, verification, sampling, others). */
+typedef struct eesd_stats {
+    int64_t rounds;
+    int64_t drafted;     /* N_all_draft */
+    int64_t accepted;    /* N_right */
+    int64_t generated;   /* L: tokens returned by eesd_generate (0 outside it) */
+    double v_d, r_d, hm; /* acceptance rate, draft proportion, their harmonic mean in percent */
+    double alpha, beta;  /* current posterior of the controller */
+    double ms_draft, ms_verify, ms_accept, ms_other; /* filled by eesd_generate */
+} eesd_stats;
+
+/*
+ * State machine:  created --prefill--> ready --draft_step (0..k_cap times)--> ready
+ *                 ready --verify--> verified --accept--> accepted --rollback--> ready
+ * Any other order returns EESD_ESTATE.  eesd_prefill may be called in any state
+ * and starts a new sequence.
+ */
+
+/* Allocates the paged KV cache (L target layers, the first N shared with the draft
+ * model, plus the early-exit layer's own cache) and all scratch memory on the current
+ * device.  hip_stream is a hipStream_t (NULL = the default stream).  Weights are
+ * borrowed.  Errors: EESD_EINVAL (null pointer, unsupported shape), EESD_ENOMEM. */
+int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* hip_stream, eesd_ctx** out);
+void eesd_destroy(eesd_ctx* ctx);
+
+/* Runs the n prompt tokens (HOST array) through all L target layers, fills the KV
+ * cache of every layer and of the early-exit layer, and draws the first generated
+ * token from the target (argmax when greedy).  That token becomes the pending token
+ * of the first round (Algorithm 1 starts from Q_g = prompt).  Synchronises.
+ * Errors: EESD_EINVAL (n < 1, token out of range), EESD_ERANGE (n + k_cap + 1 > max_seq). */
+int eesd_prefill(eesd_ctx* ctx, const int32_t* prompt, int32_t n, int32_t* first_token);
+
+/* Algorithm 1 step 6: one draft token from the draft model (Eq. 1) given everything
+ * committed and drafted so far.  The token and its probability row stay on the device;
+ * if tok_or_null is not NULL the call synchronises and returns the token.
+ * Errors: EESD_ESTATE, EESD_ERANGE (k_cap drafts already made, or cache full). */
+int eesd_draft_step(eesd_ctx* ctx, int32_t* tok_or_null);
+
+/* Algorithm 1 step 15: ONE target forward over [pending, d_1..d_K] (K = drafts since
+ * the last rollback, K = 0 allowed: a plain auto-regressive step), against the paged
+ * KV cache.  Leaves K+1 rows of target logits on the device.  Does not synchronise. */
+int eesd_verify(eesd_ctx* ctx);
+
+/* Accept / resample.  Greedy: drafts are kept while equal to the target's top-1; the
+ * next token is the top-1 after them.  Sampling: draft i is accepted iff
+ * u_i * q_i(d_i) < p_i(d_i); the first rejected position is resampled from
+ * norm(max(0, p - q)); if all K pass, a bonus token is drawn from p_{K+1}.
+ * uniforms_or_null: HOST array of K+1 doubles in [0,1) (K accept tests, then the
+ * resample/bonus draw); NULL uses the context's counter-based uniforms.
+ * Synchronises; returns a = *n_accepted and y = *next_token. */
+int eesd_accept(eesd_ctx* ctx, const double* uniforms_or_null, int32_t* n_accepted, int32_t* next_token);
+
+/* Keeps the accepted prefix: the valid length of every layer's KV cache (and of the
+ * early-exit layer's) becomes base + n_accepted + 1, whole pages past it return to the
+ * pool, the token eesd_accept returned becomes the pending token, and the controller's
+ * posterior is updated (Eq. 3-4).  0 <= n_accepted <= K else EESD_ERANGE. */
+int eesd_rollback(eesd_ctx* ctx, int32_t n_accepted);
+
+/* Algorithm 1 end to end: prefill, then rounds until max_new tokens exist.  prompt: HOST,
+ * n_prompt tokens; out: HOST buffer of at least max_new entries; *n_out = tokens written
+ * (= max_new).  stats_or_null receives the counters and time buckets of this call.
+ * Errors: as the calls above; EESD_ERANGE if n_prompt + max_new + k_cap + 1 > max_seq. */
+int eesd_generate(eesd_ctx* ctx, const int32_t* prompt, int32_t n_prompt, int32_t max_new,
+                  int32_t* out, int32_t* n_out, eesd_stats* stats_or_null);
+
+int eesd_get_stats(const eesd_ctx* ctx, eesd_stats* out);
+/* Text of the last error of this context (never NULL; static text if ctx is NULL). */
+const char* eesd_last_error(const eesd_ctx* ctx);
+
+/* ---- controller input -------------------------------------------------------------- */
+/* EESD_TS_SCHEDULE: K of round r (r = 0, 1, ...) is k_per_round[r] (HOST, copied),
+ * clipped to [1, min(k_cap, tokens still wanted)]; rounds past the end use the last entry. */
+int eesd_set_draft_schedule(eesd_ctx* ctx, const int32_t* k_per_round, int32_t n_rounds);
+/* K the controller would choose for the coming round given k_max (consumes its random draws
+ * exactly as eesd_generate does). */
+int eesd_next_draft_len(eesd_ctx* ctx, int32_t k_max, int32_t* k_out);
+
+/* ---- test and benchmark hooks ------------------------------------------------------- */
+enum {
+    EESD_READ_DRAFT_LOGITS = 0,  /* index = draft slot i (0-based): vocab floats */
+    EESD_READ_DRAFT_PROBS = 1,   /* index = draft slot: vocab floats (sampling mode only) */
+    EESD_READ_VERIFY_LOGITS = 2, /* index = verify row i (0..K): vocab floats */
+    EESD_READ_KV_K = 3,          /* index = layer (n_layers = the early-exit layer): kv_len x n_kv_heads x head_dim floats */
+    EESD_READ_KV_V = 4,
+    EESD_READ_TOKENS = 5,        /* the block [pending, d_1..d_K] as int32 */
+    EESD_READ_KV_LEN = 6,        /* one int32 */
+    EESD_READ_PAGE_TABLE = 7     /* ceil(max_seq / kv_page) int32 (-1 = unmapped) */
+};
+/* Copies internal state to HOST memory as fp32 / int32.  Synchronises.  n_tokens limits KV reads. */
+int eesd_debug_read(eesd_ctx* ctx, int what, int index, int32_t n_tokens, void* host_dst, size_t bytes);
+/* Teacher forcing: the next n draft steps emit toks[i] instead of the token they sample
+ * (their logits and probability rows are still those of the draft model). */
+int eesd_debug_force_drafts(eesd_ctx* ctx, const int32_t* toks, int32_t n);
+/* Teacher forcing: replaces the pending token (state must be ready). */
+int eesd_debug_force_pending(eesd_ctx* ctx, int32_t tok);
+/* Fills KV rows [0, n_tokens) of every cache with a cheap deterministic pattern and sets
+ * kv_len = n_tokens, pending = tok: a stand-in for a prefilled cache in micro-benchmarks. */
+int eesd_debug_fill_cache(eesd_ctx* ctx, int32_t n_tokens, int32_t pending_tok);
+
+/* Launch-shape knobs for benchmark sweeps (process-wide; 0 restores the built-in heuristic):
+ * "valu_nw", "valu_tpw", "valu_rp", "mfma_t", "mfma_nw", "attn_split", "mfma_min_m". */
+int eesd_set_tunable(const char* name, int value);
+
+/* ---- stand-alone kernels (device buffers in, host results out) ----------------------- */
+/* The accept/resample decision on given probability rows (sampling) or logit rows (greedy).
+ * p_rows: DEVICE fp32 [K+1][vocab]; q_rows: DEVICE fp32 [K][vocab] (ignored when greedy);
+ * drafts: DEVICE int32 [K]; uniforms: HOST double [K+1]; result: HOST int32[2] = {a, y}. */
+int eesd_op_accept(const float* p_rows, const float* q_rows, const int32_t* drafts, const double* uniforms,
+                   int32_t K, int32_t vocab, int32_t greedy, void* hip_stream, int32_t* result);
+/* softmax(logits / temperature) of one DEVICE fp32 row into probs (DEVICE fp32), then an
+ * inverse-CDF draw with u (temperature 0: argmax, probs untouched).  *token: HOST. */
+int eesd_op_softmax_sample(const float* logits, float* probs, int32_t vocab, float temperature, double u,
+                           void* hip_stream, int32_t* token);
+/* Y[m][r] = sum_k X[m][k] W[r][k] for M <= 16 rows: the weight-streaming product of the draft
+ * (M = 1) and verify (M = K+1) passes without prologue or epilogue.  W: DEVICE [out][in] in
+ * dtype; X: DEVICE fp32 [M][in]; Y: DEVICE fp32 [M][out]; path: EESD_GEMM_*. */
+int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,
+                 int32_t dtype, int32_t path, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EESD_H */

@@ -192,7 +192,7 @@ def decide_accept(p_rows: np.ndarray, q_rows: Optional[np.ndarray], drafts: Sequ
             a += 1
         return a, argmax_lowest(p_rows[a])
     p32 = p_rows.astype(np.float32)
-    q32 = q_rows.astype(np.float32)
+    q32 = q_rows.astype(np.float32) if K else None      # K = 0: a plain target step, no draft rows
     while a < K:
         d = int(drafts[a])
         if F64(u_acc[a]) * F64(q32[a, d]) < F64(p32[a, d]):
@@ -408,7 +408,7 @@ class OracleEESD:
             u_acc = [uniform(self.seed, STREAM_ACCEPT, self.rnd, i) for i in range(K)]
         if u_res is None:
             u_res = uniform(self.seed, STREAM_RESAMPLE, self.rnd)
-        q = None if self.greedy else np.stack(self.q_rows)
+        q = None if (self.greedy or K == 0) else np.stack(self.q_rows)
         self.last = decide_accept(self.p_rows, q, self.drafts, u_acc, u_res, self.greedy)
         return self.last
 

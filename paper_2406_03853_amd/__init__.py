@@ -1,0 +1,10 @@
+"""MI355X (gfx950) hot path of Early-exiting Speculative Decoding.
+
+Every step of a decoding round runs in the HIP library `libeesd.so` (C ABI in
+include/eesd.h); this package is a thin ctypes binding with the same names.
+PyTorch is used by callers only to own device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    EESD, EesdError, Stats, lib, lib_path, op_accept, op_gemm, op_softmax_sample, set_tunable,
+    DTYPE_F32, DTYPE_BF16, TS_BETA, TS_FIXED, TS_SCHEDULE, GEMM_AUTO, GEMM_VALU, GEMM_MFMA,
+)

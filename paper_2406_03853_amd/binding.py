@@ -1,0 +1,295 @@
+"""ctypes binding of libeesd.so: argument marshalling only.
+
+The names follow include/eesd.h.  Nothing here computes: if the library is not
+built the import of `lib()` raises, there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+DTYPE_F32, DTYPE_BF16 = 0, 1
+TS_BETA, TS_FIXED, TS_SCHEDULE = 0, 1, 2
+GEMM_AUTO, GEMM_VALU, GEMM_MFMA = 0, 1, 2
+READ_DRAFT_LOGITS, READ_DRAFT_PROBS, READ_VERIFY_LOGITS, READ_KV_K, READ_KV_V, READ_TOKENS, READ_KV_LEN, READ_PAGE_TABLE = range(8)
+
+_STATUS = {0: "EESD_OK", -1: "EESD_EINVAL", -2: "EESD_ENOMEM", -3: "EESD_ESTATE", -4: "EESD_ERANGE", -5: "EESD_EDEVICE"}
+
+
+class EesdError(RuntimeError):
+    def __init__(self, code: int, text: str = ""):
+        super().__init__(f"{_STATUS.get(code, code)}: {text}")
+        self.code = code
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_draft_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("vocab", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_seq", C.c_int32),
+                ("kv_page", C.c_int32), ("k_cap", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
+                ("ts_alpha0", C.c_double), ("ts_beta0", C.c_double), ("ts_mode", C.c_int32), ("ts_update", C.c_int32),
+                ("gemm_path", C.c_int32), ("reserved", C.c_int32)]
+
+
+class _Layer(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("layers", C.POINTER(_Layer)), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p),
+                ("ee_layer", _Layer), ("ee_norm", C.c_void_p), ("ee_head", C.c_void_p)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("rounds", C.c_int64), ("drafted", C.c_int64), ("accepted", C.c_int64), ("generated", C.c_int64),
+                ("v_d", C.c_double), ("r_d", C.c_double), ("hm", C.c_double), ("alpha", C.c_double), ("beta", C.c_double),
+                ("ms_draft", C.c_double), ("ms_verify", C.c_double), ("ms_accept", C.c_double), ("ms_other", C.c_double)]
+
+
+@dataclass
+class Stats:
+    rounds: int
+    drafted: int
+    accepted: int
+    generated: int
+    v_d: float
+    r_d: float
+    hm: float
+    alpha: float
+    beta: float
+    ms_draft: float
+    ms_verify: float
+    ms_accept: float
+    ms_other: float
+
+
+def lib_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libeesd.so")
+
+
+_LIB = None
+EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_rollback",
+           "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
+           "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
+           "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
+
+
+def lib() -> C.CDLL:
+    """Loads libeesd.so (built by paper_2406_03853_amd/build.py).  Raises if it is missing."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is not built: run `python -m paper_2406_03853_amd.build`")
+    L = C.CDLL(path)
+    P, I32, VP = C.POINTER, C.c_int32, C.c_void_p
+    L.eesd_create.argtypes = [P(_Config), P(_Weights), VP, P(VP)]
+    L.eesd_destroy.argtypes = [VP]
+    L.eesd_destroy.restype = None
+    L.eesd_prefill.argtypes = [VP, P(I32), I32, P(I32)]
+    L.eesd_draft_step.argtypes = [VP, P(I32)]
+    L.eesd_verify.argtypes = [VP]
+    L.eesd_accept.argtypes = [VP, P(C.c_double), P(I32), P(I32)]
+    L.eesd_rollback.argtypes = [VP, I32]
+    L.eesd_generate.argtypes = [VP, P(I32), I32, I32, P(I32), P(I32), P(_Stats)]
+    L.eesd_get_stats.argtypes = [VP, P(_Stats)]
+    L.eesd_last_error.argtypes = [VP]
+    L.eesd_last_error.restype = C.c_char_p
+    L.eesd_set_draft_schedule.argtypes = [VP, P(I32), I32]
+    L.eesd_next_draft_len.argtypes = [VP, I32, P(I32)]
+    L.eesd_debug_read.argtypes = [VP, C.c_int, C.c_int, I32, VP, C.c_size_t]
+    L.eesd_debug_force_drafts.argtypes = [VP, P(I32), I32]
+    L.eesd_debug_force_pending.argtypes = [VP, I32]
+    L.eesd_debug_fill_cache.argtypes = [VP, I32, I32]
+    L.eesd_set_tunable.argtypes = [C.c_char_p, C.c_int]
+    L.eesd_op_accept.argtypes = [VP, VP, VP, P(C.c_double), I32, I32, I32, VP, P(I32)]
+    L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
+    L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, VP]
+    for name in EXPORTS:
+        if name not in ("eesd_destroy", "eesd_last_error"):
+            getattr(L, name).restype = C.c_int
+    _LIB = L
+    return L
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _ptr(arr: np.ndarray, ct):
+    return arr.ctypes.data_as(C.POINTER(ct))
+
+
+def set_tunable(name: str, value: int) -> None:
+    rc = lib().eesd_set_tunable(name.encode(), int(value))
+    if rc:
+        raise EesdError(rc, f"unknown tunable {name}")
+
+
+class EESD:
+    """One decoding context.  `weights` is the dict layout of synth_inputs.make_weights with
+    torch tensors on the GPU; the tensors are borrowed by the library and kept alive here."""
+
+    def __init__(self, weights: dict, max_seq: int, temperature: float, seed: int = 0, k_cap: int = 10,
+                 kv_page: int = 16, alpha0: float = 1.0, beta0: float = 1.0, ts_mode: int = TS_BETA,
+                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0):
+        sh = weights["shape"]
+        self._keep = weights
+        self.shape = sh
+        self.vocab = sh["vocab"]
+        cfg = _Config(sh["n_layers"], sh["n_draft_layers"], sh["d_model"], sh["n_heads"], sh["n_kv_heads"], sh["head_dim"],
+                      sh["d_ff"], sh["vocab"], sh["rms_eps"], sh["rope_base"], DTYPE_BF16 if sh["dtype"] == "bf16" else DTYPE_F32,
+                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, 0)
+
+        def lw(d):
+            return _Layer(*[d[k].data_ptr() for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
+        self._layers = (_Layer * sh["n_layers"])(*[lw(l) for l in weights["layers"]])
+        w = _Weights(weights["tok_emb"].data_ptr(), self._layers, weights["final_norm"].data_ptr(), weights["lm_head"].data_ptr(),
+                     lw(weights["ee_layer"]), weights["ee_norm"].data_ptr(), weights["ee_head"].data_ptr())
+        self._h = C.c_void_p()
+        rc = lib().eesd_create(C.byref(cfg), C.byref(w), C.c_void_p(stream), C.byref(self._h))
+        if rc:
+            self._h = None
+            raise EesdError(rc, "eesd_create")
+        self.k_cap = k_cap
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().eesd_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def _ck(self, rc: int):
+        if rc:
+            raise EesdError(rc, lib().eesd_last_error(self._h).decode())
+
+    # the calls of a round -------------------------------------------------------------------
+    def prefill(self, prompt) -> int:
+        p = _i32(prompt)
+        tok = C.c_int32()
+        self._ck(lib().eesd_prefill(self._h, _ptr(p, C.c_int32), len(p), C.byref(tok)))
+        return tok.value
+
+    def draft_step(self, sync: bool = True) -> Optional[int]:
+        if not sync:
+            self._ck(lib().eesd_draft_step(self._h, None))
+            return None
+        tok = C.c_int32()
+        self._ck(lib().eesd_draft_step(self._h, C.byref(tok)))
+        return tok.value
+
+    def verify(self) -> None:
+        self._ck(lib().eesd_verify(self._h))
+
+    def accept(self, uniforms: Optional[Sequence[float]] = None):
+        a, y = C.c_int32(), C.c_int32()
+        if uniforms is None:
+            self._ck(lib().eesd_accept(self._h, None, C.byref(a), C.byref(y)))
+        else:
+            u = np.ascontiguousarray(np.asarray(uniforms, dtype=np.float64))
+            self._ck(lib().eesd_accept(self._h, _ptr(u, C.c_double), C.byref(a), C.byref(y)))
+        return a.value, y.value
+
+    def rollback(self, n_accepted: int) -> None:
+        self._ck(lib().eesd_rollback(self._h, int(n_accepted)))
+
+    def generate(self, prompt, max_new: int):
+        p = _i32(prompt)
+        out = np.zeros(max_new, np.int32)
+        n = C.c_int32()
+        st = _Stats()
+        self._ck(lib().eesd_generate(self._h, _ptr(p, C.c_int32), len(p), max_new, _ptr(out, C.c_int32), C.byref(n), C.byref(st)))
+        return out[: n.value].tolist(), Stats(*[getattr(st, f[0]) for f in _Stats._fields_])
+
+    def stats(self) -> Stats:
+        st = _Stats()
+        self._ck(lib().eesd_get_stats(self._h, C.byref(st)))
+        return Stats(*[getattr(st, f[0]) for f in _Stats._fields_])
+
+    # controller ---------------------------------------------------------------------------------
+    def set_draft_schedule(self, ks) -> None:
+        k = _i32(ks)
+        self._ck(lib().eesd_set_draft_schedule(self._h, _ptr(k, C.c_int32), len(k)))
+
+    def next_draft_len(self, k_max: int) -> int:
+        k = C.c_int32()
+        self._ck(lib().eesd_next_draft_len(self._h, k_max, C.byref(k)))
+        return k.value
+
+    # hooks ---------------------------------------------------------------------------------------
+    def force_drafts(self, toks) -> None:
+        t = _i32(toks)
+        self._ck(lib().eesd_debug_force_drafts(self._h, _ptr(t, C.c_int32), len(t)))
+
+    def force_pending(self, tok: int) -> None:
+        self._ck(lib().eesd_debug_force_pending(self._h, int(tok)))
+
+    def fill_cache(self, n_tokens: int, pending: int = 1) -> None:
+        self._ck(lib().eesd_debug_fill_cache(self._h, int(n_tokens), int(pending)))
+
+    def _read(self, what: int, index: int, n_tokens: int, arr: np.ndarray) -> np.ndarray:
+        self._ck(lib().eesd_debug_read(self._h, what, index, n_tokens, arr.ctypes.data_as(C.c_void_p), arr.nbytes))
+        return arr
+
+    def draft_logits(self, slot: int) -> np.ndarray:
+        return self._read(READ_DRAFT_LOGITS, slot, 0, np.empty(self.vocab, np.float32))
+
+    def draft_probs(self, slot: int) -> np.ndarray:
+        return self._read(READ_DRAFT_PROBS, slot, 0, np.empty(self.vocab, np.float32))
+
+    def verify_logits(self, row: int) -> np.ndarray:
+        return self._read(READ_VERIFY_LOGITS, row, 0, np.empty(self.vocab, np.float32))
+
+    def kv(self, cache: int, n_tokens: int):
+        sh = self.shape
+        k = self._read(READ_KV_K, cache, n_tokens, np.empty((n_tokens, sh["n_kv_heads"], sh["head_dim"]), np.float32))
+        v = self._read(READ_KV_V, cache, n_tokens, np.empty((n_tokens, sh["n_kv_heads"], sh["head_dim"]), np.float32))
+        return k, v
+
+    def kv_len(self) -> int:
+        return int(self._read(READ_KV_LEN, 0, 0, np.empty(1, np.int32))[0])
+
+    def block_tokens(self, n: int) -> List[int]:
+        return self._read(READ_TOKENS, 0, 0, np.empty(n, np.int32)).tolist()
+
+    def page_table(self, n_pages: int) -> List[int]:
+        return self._read(READ_PAGE_TABLE, 0, 0, np.empty(n_pages, np.int32)).tolist()
+
+
+# stand-alone kernels: torch tensors on the GPU in, Python values out ------------------------------
+def op_accept(p_rows, q_rows, drafts, uniforms, greedy: bool, stream: int = 0):
+    K = int(drafts.numel())
+    V = int(p_rows.shape[-1])
+    res = np.zeros(2, np.int32)
+    u = np.ascontiguousarray(np.asarray(uniforms if uniforms is not None else np.zeros(K + 1), dtype=np.float64))
+    rc = lib().eesd_op_accept(p_rows.data_ptr(), q_rows.data_ptr() if q_rows is not None else None, drafts.data_ptr(),
+                              _ptr(u, C.c_double), K, V, int(greedy), C.c_void_p(stream), _ptr(res, C.c_int32))
+    if rc:
+        raise EesdError(rc, "eesd_op_accept")
+    return int(res[0]), int(res[1])
+
+
+def op_softmax_sample(logits, probs, temperature: float, u: float, stream: int = 0) -> int:
+    tok = C.c_int32()
+    rc = lib().eesd_op_softmax_sample(logits.data_ptr(), probs.data_ptr() if probs is not None else None, int(logits.numel()),
+                                      float(temperature), float(u), C.c_void_p(stream), C.byref(tok))
+    if rc:
+        raise EesdError(rc, "eesd_op_softmax_sample")
+    return tok.value
+
+
+def op_gemm(W, X, Y, path: int = GEMM_AUTO, stream: int = 0) -> None:
+    import torch
+    M, inn = X.shape
+    out = W.shape[0]
+    dt = DTYPE_BF16 if W.dtype == torch.bfloat16 else DTYPE_F32
+    rc = lib().eesd_op_gemm(W.data_ptr(), X.data_ptr(), Y.data_ptr(), M, out, inn, dt, path, C.c_void_p(stream))
+    if rc:
+        raise EesdError(rc, "eesd_op_gemm")

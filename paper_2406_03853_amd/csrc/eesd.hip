@@ -1,0 +1,1114 @@
+// Host side of the EESD library: context, paged KV cache, pass drivers, the round's calls,
+// the Beta-posterior controller and the generation loop.  C ABI in include/eesd.h.
+#include "../../include/eesd.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "attention.hiph"
+#include "common.hiph"
+#include "gemm.hiph"
+#include "sampling.hiph"
+
+#define MAX_ROWS 16  // rows per pass: 1 (draft) .. k_cap + 1 (verify), prefill chunk
+
+// ---------------------------------------------------------------------------------------------
+// tunables (benchmark sweeps)
+// ---------------------------------------------------------------------------------------------
+static int g_valu_nw = 0;      // waves per workgroup of the VALU product (0 = heuristic)
+static int g_valu_tpw = 0;     // tasks per wave
+static int g_valu_rp = 0;      // row pairs per task (1 or 2)
+static int g_mfma_t = 0;       // 16-row tiles per block half (1 or 2)
+static int g_mfma_nw = 0;      // waves per workgroup of the MFMA product
+static int g_attn_split = 0;   // keys per attention split
+static int g_mfma_min_m = 2;   // AUTO: smallest M that takes the MFMA family on bf16 weights
+
+extern "C" int eesd_set_tunable(const char* name, int value) {
+    if (!name) return EESD_EINVAL;
+    struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
+                                             {"mfma_t", &g_mfma_t}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
+                                             {"mfma_min_m", &g_mfma_min_m}};
+    for (auto& e : t)
+        if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
+    return EESD_EINVAL;
+}
+
+// ---------------------------------------------------------------------------------------------
+// counter-based uniforms: splitmix64 output function of a key built from
+// (seed, stream, round, slot, sub); u = top 53 bits * 2^-53
+// ---------------------------------------------------------------------------------------------
+enum { STREAM_DRAFT = 1, STREAM_ACCEPT = 2, STREAM_RESAMPLE = 3, STREAM_TS_THETA = 4, STREAM_TS_CHI = 5 };
+
+static inline uint64_t splitmix64(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+static inline double uniform53(uint64_t seed, int stream, int64_t rnd, int slot, int sub) {
+    uint64_t key = seed ^ ((uint64_t)(stream & 0xFF) << 56) ^ ((uint64_t)(rnd & 0xFFFFFF) << 32) ^
+                   ((uint64_t)(slot & 0xFF) << 24) ^ (uint64_t)(sub & 0xFFFFFF);
+    return (double)(splitmix64(key) >> 11) * (1.0 / 9007199254740992.0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------------------------
+enum State { ST_CREATED = 0, ST_READY, ST_VERIFIED, ST_ACCEPTED };
+
+struct eesd_ctx {
+    eesd_config cfg;
+    std::vector<eesd_layer_weights> layers;
+    eesd_weights w;
+    hipStream_t stream;
+    int device;
+    std::string err;
+
+    // sequence state
+    State state;
+    int kv_len;       // tokens whose K/V are valid in every cache
+    int n_drafted;    // drafts since the last rollback
+    int64_t round;    // 0 = prefill, 1.. = decoding rounds
+    int last_a, last_y;
+    std::vector<int32_t> forced;  // teacher-forced draft tokens (consumed front first)
+    size_t forced_pos;
+
+    // controller
+    double alpha, beta;
+    std::vector<int32_t> schedule;
+    int64_t sched_round;
+    eesd_stats stats;
+
+    // paged KV cache
+    int n_caches;            // L + 1
+    int n_pages, page_tokens, page_shift;
+    long long page_stride;   // elements
+    size_t elem;             // bytes per cache element
+    void* kv_pool;
+    int32_t* d_table;        // device page table
+    int32_t* h_table;        // pinned host mirror
+    std::vector<int32_t> free_pages;
+    int mapped_pages;
+
+    // scratch (device)
+    float *x, *q, *attn, *act, *logits, *p_rows, *q_logits, *q_rows, *part_o, *part_ml, *rope_cs;
+    bf16_t *xb, *ab, *actb;
+    int32_t *blk_tok, *prompt_dev, *result_dev;
+    int32_t *h_result, *h_prompt;  // pinned
+    int max_splits;
+    hipEvent_t ev[4];
+};
+
+static int fail(eesd_ctx* c, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf;
+    return code;
+}
+
+#define HIP_TRY(c, call)                                                                            \
+    do {                                                                                            \
+        hipError_t e__ = (call);                                                                    \
+        if (e__ != hipSuccess) return fail((c), EESD_EDEVICE, "%s: %s", #call, hipGetErrorString(e__)); \
+    } while (0)
+
+static inline bool is_bf16(const eesd_ctx* c) { return c->cfg.dtype == EESD_DTYPE_BF16; }
+
+static KVView kv_view(const eesd_ctx* c, int cache) {
+    KVView v;
+    v.pool = c->kv_pool;
+    v.table = c->d_table;
+    v.page_stride = c->page_stride;
+    long long blk = (long long)c->cfg.n_kv_heads * c->page_tokens * c->cfg.head_dim;
+    v.k_off = (long long)(cache * 2) * blk;
+    v.v_off = (long long)(cache * 2 + 1) * blk;
+    v.page_tokens = c->page_tokens;
+    v.page_shift = c->page_shift;
+    v.n_kv_heads = c->cfg.n_kv_heads;
+    v.head_dim = c->cfg.head_dim;
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// kernel launchers
+// ---------------------------------------------------------------------------------------------
+// Dynamic LDS above the default limit has to be granted per kernel; remember what was granted.
+static hipError_t allow_lds(const void* fn, size_t bytes) {
+    static std::vector<std::pair<const void*, size_t>> done;
+    if (bytes <= 48 * 1024) return hipSuccess;
+    for (auto& p : done)
+        if (p.first == fn) {
+            if (p.second >= bytes) return hipSuccess;
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e == hipSuccess) p.second = bytes;
+            return e;
+        }
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) done.push_back({fn, bytes});
+    return e;
+}
+
+template <typename WT, int MT, int EPI, int RP>
+static hipError_t launch_valu_t(const GemmP& p, hipStream_t st) {
+    int n_tasks = (p.out_rows / 2) / RP;
+    size_t lds = ((size_t)MT * p.in_dim + MT) * sizeof(float);
+    if (lds > 150 * 1024) return hipErrorInvalidValue;
+    int nw = g_valu_nw ? g_valu_nw : (lds > 40 * 1024 ? 16 : 4);
+    int tpw = g_valu_tpw ? g_valu_tpw : std::max(1, std::min(8, n_tasks / 8192));
+    int grid = (n_tasks + nw * tpw - 1) / (nw * tpw);
+    auto fn = gemm_valu_kernel<WT, MT, EPI, RP>;
+    hipError_t e = allow_lds((const void*)fn, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(nw * 64), lds, st, p, n_tasks, tpw);
+    return hipGetLastError();
+}
+
+template <typename WT, int EPI>
+static hipError_t launch_valu_m(const GemmP& p, hipStream_t st) {
+    bool rp2 = g_valu_rp ? g_valu_rp == 2 : true;
+    // pairs per task must divide the pairs of a head half (QKV) and the pair count
+    int n_pairs = p.out_rows / 2;
+    if (EPI == EPI_QKV && ((p.head_dim / 2) % 2)) rp2 = false;
+    if (n_pairs % 2) rp2 = false;
+    if (p.M <= 1) return rp2 ? launch_valu_t<WT, 1, EPI, 2>(p, st) : launch_valu_t<WT, 1, EPI, 1>(p, st);
+    if (p.M <= 2) return rp2 ? launch_valu_t<WT, 2, EPI, 2>(p, st) : launch_valu_t<WT, 2, EPI, 1>(p, st);
+    if (p.M <= 4) return rp2 ? launch_valu_t<WT, 4, EPI, 2>(p, st) : launch_valu_t<WT, 4, EPI, 1>(p, st);
+    if (p.M <= 8) return launch_valu_t<WT, 8, EPI, 1>(p, st);
+    return launch_valu_t<WT, 16, EPI, 1>(p, st);
+}
+
+static size_t valu_lds_bytes(int M, int in) {
+    int mt = M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : M <= 8 ? 8 : 16;
+    return ((size_t)mt * in + mt) * sizeof(float);
+}
+
+template <int EPI>
+static hipError_t launch_valu(const GemmP& p, bool bf16, hipStream_t st) {
+    return bf16 ? launch_valu_m<bf16_t, EPI>(p, st) : launch_valu_m<float, EPI>(p, st);
+}
+
+template <int EPI>
+static hipError_t launch_mfma(const GemmP& p, hipStream_t st) {
+    int unit = (EPI == EPI_QKV) ? p.head_dim / 2 : p.out_rows / 2;
+    // T tiles of 16 rows per block half: 16*T must divide `unit`
+    int T = g_mfma_t ? g_mfma_t : ((p.out_rows / 64) >= 2048 ? 2 : 1);
+    if (unit % (16 * T)) T = 1;
+    int n_blocks = p.out_rows / (32 * T);
+    int steps = p.in_dim / 128;
+    int nw = g_mfma_nw;
+    if (!nw) {
+        nw = 1;
+        while (nw * 2 <= 16 && nw * 2 * 4 <= steps) nw *= 2;
+    }
+    nw = std::max(nw, T);
+    nw = std::min(nw, std::max(steps, T));
+    size_t lds = (size_t)nw * 2 * T * 64 * 16;
+    if (T == 2) {
+        auto fn = gemm_mfma_kernel<EPI, 2>;
+        hipError_t e = allow_lds((const void*)fn, lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(fn, dim3(n_blocks), dim3(nw * 64), lds, st, p);
+    } else {
+        auto fn = gemm_mfma_kernel<EPI, 1>;
+        hipError_t e = allow_lds((const void*)fn, lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(fn, dim3(n_blocks), dim3(nw * 64), lds, st, p);
+    }
+    return hipGetLastError();
+}
+
+static bool mfma_shape_ok(int out, int in, int epi, int head_dim) {
+    if (in % 128) return false;
+    if (epi == EPI_QKV) return head_dim % 32 == 0 && out % head_dim == 0;
+    if (epi == EPI_SWIGLU) return (out / 2) % 16 == 0;
+    return out % 32 == 0;
+}
+
+// true -> MFMA family
+static bool pick_mfma(const eesd_ctx* c, int M) {
+    if (!is_bf16(c)) return false;
+    if (c->cfg.gemm_path == EESD_GEMM_VALU) return false;
+    if (c->cfg.gemm_path == EESD_GEMM_MFMA) return true;
+    return M >= g_mfma_min_m;
+}
+
+static GemmP gemm_base(const void* W, const void* X, int ldx, int M, int out, int in) {
+    GemmP p;
+    memset(&p, 0, sizeof p);
+    p.W = W; p.X = X; p.ldx = ldx; p.M = M; p.out_rows = out; p.in_dim = in;
+    return p;
+}
+
+static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf16) {
+    const eesd_config& g = c->cfg;
+    AttnP a;
+    memset(&a, 0, sizeof a);
+    a.Q = c->q;
+    a.kv = kv_view(c, cache);
+    a.M = M; a.pos0 = pos0;
+    a.n_heads = g.n_heads; a.n_kv_heads = g.n_kv_heads; a.head_dim = g.head_dim;
+    int n_keys = pos0 + M;
+    int group = g.n_heads / g.n_kv_heads;
+    int qblocks = (M * group + ATT_QG - 1) / ATT_QG;
+    // enough workgroups to cover the chip, splits of at least 2 tiles
+    int split_len = g_attn_split;
+    if (!split_len) {
+        int want = std::max(1, 1024 / std::max(1, g.n_kv_heads * qblocks));
+        split_len = (n_keys + want - 1) / want;
+        split_len = std::max(2 * ATT_TT, (split_len + ATT_TT - 1) / ATT_TT * ATT_TT);
+    }
+    int n_splits = (n_keys + split_len - 1) / split_len;
+    if (n_splits > c->max_splits) {
+        n_splits = c->max_splits;
+        split_len = ((n_keys + n_splits - 1) / n_splits + ATT_TT - 1) / ATT_TT * ATT_TT;
+        n_splits = (n_keys + split_len - 1) / split_len;
+    }
+    a.n_splits = n_splits; a.split_len = split_len;
+    a.scale = 1.0f / sqrtf((float)g.head_dim);
+    a.out = out_bf16 ? (void*)c->ab : (void*)c->attn;
+    a.out_bf16 = out_bf16;
+    a.part_o = c->part_o; a.part_ml = c->part_ml;
+    dim3 grid(n_splits * g.n_kv_heads, qblocks);
+    bool kb = is_bf16(c);
+    if (g.head_dim == 128) {
+        if (kb) hipLaunchKernelGGL((attn_split_kernel<bf16_t, 128>), grid, dim3(ATT_THREADS), 0, c->stream, a);
+        else hipLaunchKernelGGL((attn_split_kernel<float, 128>), grid, dim3(ATT_THREADS), 0, c->stream, a);
+    } else {
+        if (kb) hipLaunchKernelGGL((attn_split_kernel<bf16_t, 64>), grid, dim3(ATT_THREADS), 0, c->stream, a);
+        else hipLaunchKernelGGL((attn_split_kernel<float, 64>), grid, dim3(ATT_THREADS), 0, c->stream, a);
+    }
+    HIP_TRY(c, hipGetLastError());
+    if (n_splits > 1) {
+        if (g.head_dim == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M * g.n_heads), dim3(128), 0, c->stream, a);
+        else hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(M * g.n_heads), dim3(64), 0, c->stream, a);
+        HIP_TRY(c, hipGetLastError());
+    }
+    return EESD_OK;
+}
+
+static int launch_rmsnorm_bf16(eesd_ctx* c, const float* x, int M, const void* gain, bf16_t* out, int ld) {
+    int d = c->cfg.d_model;
+    hipLaunchKernelGGL((rmsnorm_bf16_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->stream, x, d, (const bf16_t*)gain, c->cfg.rms_eps, d,
+                       out, ld);
+    HIP_TRY(c, hipGetLastError());
+    return EESD_OK;
+}
+
+static void fill_qkv(eesd_ctx* c, GemmP& p, int cache, int pos0, int head0) {
+    p.Q = c->q;
+    p.n_heads = c->cfg.n_heads; p.n_kv_heads = c->cfg.n_kv_heads; p.head_dim = c->cfg.head_dim;
+    p.head0 = head0; p.pos0 = pos0; p.rope_cs = c->rope_cs;
+    p.kv = kv_view(c, cache);
+    p.kv_bf16 = is_bf16(c);
+}
+
+// One decoder layer on the M rows in c->x at positions pos0.. ; K/V go to `cache`.
+static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M, int pos0, bool mfma) {
+    const eesd_config& g = c->cfg;
+    const int d = g.d_model, hd = g.head_dim, qd = g.n_heads * hd, f = g.d_ff;
+    const int qkv_rows = (g.n_heads + 2 * g.n_kv_heads) * hd;
+    const bool b16 = is_bf16(c);
+    if (mfma) {
+        int rc = launch_rmsnorm_bf16(c, c->x, M, lw.attn_norm, c->xb, d);
+        if (rc) return rc;
+        GemmP p = gemm_base(lw.wqkv, c->xb, d, M, qkv_rows, d);
+        fill_qkv(c, p, cache, pos0, 0);
+        HIP_TRY(c, launch_mfma<EPI_QKV>(p, c->stream));
+        rc = launch_attention(c, cache, M, pos0, true);
+        if (rc) return rc;
+        p = gemm_base(lw.wo, c->ab, qd, M, d, qd);
+        p.Y = c->x; p.ldy = d;
+        HIP_TRY(c, launch_mfma<EPI_RESID>(p, c->stream));
+        rc = launch_rmsnorm_bf16(c, c->x, M, lw.ffn_norm, c->xb, d);
+        if (rc) return rc;
+        p = gemm_base(lw.w_gate_up, c->xb, d, M, 2 * f, d);
+        p.Y = c->actb; p.ldy = f; p.y_bf16 = 1;
+        HIP_TRY(c, launch_mfma<EPI_SWIGLU>(p, c->stream));
+        p = gemm_base(lw.w_down, c->actb, f, M, d, f);
+        p.Y = c->x; p.ldy = d;
+        HIP_TRY(c, launch_mfma<EPI_RESID>(p, c->stream));
+    } else {
+        GemmP p = gemm_base(lw.wqkv, c->x, d, M, qkv_rows, d);
+        p.gain = lw.attn_norm; p.eps = g.rms_eps;
+        fill_qkv(c, p, cache, pos0, 0);
+        HIP_TRY(c, launch_valu<EPI_QKV>(p, b16, c->stream));
+        int rc = launch_attention(c, cache, M, pos0, false);
+        if (rc) return rc;
+        p = gemm_base(lw.wo, c->attn, qd, M, d, qd);
+        p.Y = c->x; p.ldy = d;
+        HIP_TRY(c, launch_valu<EPI_RESID>(p, b16, c->stream));
+        p = gemm_base(lw.w_gate_up, c->x, d, M, 2 * f, d);
+        p.gain = lw.ffn_norm; p.eps = g.rms_eps;
+        p.Y = c->act; p.ldy = f; p.y_bf16 = 0;
+        HIP_TRY(c, launch_valu<EPI_SWIGLU>(p, b16, c->stream));
+        p = gemm_base(lw.w_down, c->act, f, M, d, f);
+        p.Y = c->x; p.ldy = d;
+        HIP_TRY(c, launch_valu<EPI_RESID>(p, b16, c->stream));
+    }
+    return EESD_OK;
+}
+
+// Keys and values of the early-exit layer for the M rows in c->x (layer-N hidden states):
+// only the k and v rows of its fused QKV matrix are streamed.
+static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
+    const eesd_config& g = c->cfg;
+    const int d = g.d_model, hd = g.head_dim;
+    const size_t esz = is_bf16(c) ? 2 : 4;
+    const char* wkv = (const char*)c->w.ee_layer.wqkv + (size_t)g.n_heads * hd * d * esz;
+    const int rows = 2 * g.n_kv_heads * hd;
+    if (mfma) {
+        int rc = launch_rmsnorm_bf16(c, c->x, M, c->w.ee_layer.attn_norm, c->xb, d);
+        if (rc) return rc;
+        GemmP p = gemm_base(wkv, c->xb, d, M, rows, d);
+        fill_qkv(c, p, g.n_layers, pos0, g.n_heads);
+        HIP_TRY(c, launch_mfma<EPI_QKV>(p, c->stream));
+    } else {
+        GemmP p = gemm_base(wkv, c->x, d, M, rows, d);
+        p.gain = c->w.ee_layer.attn_norm; p.eps = g.rms_eps;
+        fill_qkv(c, p, g.n_layers, pos0, g.n_heads);
+        HIP_TRY(c, launch_valu<EPI_QKV>(p, is_bf16(c), c->stream));
+    }
+    return EESD_OK;
+}
+
+// logits[m][:] = RMSNorm(x[m]; norm) head^T for rows x0 .. x0+M-1 of c->x
+static int run_head(eesd_ctx* c, const void* norm, const void* head, int x0, int M, float* logits, bool mfma) {
+    const eesd_config& g = c->cfg;
+    const int d = g.d_model;
+    const float* xr = c->x + (size_t)x0 * d;
+    if (mfma) {
+        int rc = launch_rmsnorm_bf16(c, xr, M, norm, c->xb, d);
+        if (rc) return rc;
+        GemmP p = gemm_base(head, c->xb, d, M, g.vocab, d);
+        p.Y = logits; p.ldy = g.vocab;
+        HIP_TRY(c, launch_mfma<EPI_PLAIN>(p, c->stream));
+    } else {
+        GemmP p = gemm_base(head, xr, d, M, g.vocab, d);
+        p.gain = norm; p.eps = g.rms_eps;
+        p.Y = logits; p.ldy = g.vocab;
+        HIP_TRY(c, launch_valu<EPI_PLAIN>(p, is_bf16(c), c->stream));
+    }
+    return EESD_OK;
+}
+
+static int launch_embed(eesd_ctx* c, const int32_t* tok_dev, int M) {
+    const int d = c->cfg.d_model;
+    dim3 grid((d + 255) / 256, M);
+    if (is_bf16(c)) hipLaunchKernelGGL((embed_kernel<bf16_t>), grid, dim3(256), 0, c->stream, (const bf16_t*)c->w.tok_emb, tok_dev, d, c->x, d);
+    else hipLaunchKernelGGL((embed_kernel<float>), grid, dim3(256), 0, c->stream, (const float*)c->w.tok_emb, tok_dev, d, c->x, d);
+    HIP_TRY(c, hipGetLastError());
+    return EESD_OK;
+}
+
+// Target forward over M rows whose tokens are tok_dev[0..M) at positions pos0.. :
+// all L layers (plus the early-exit layer's K/V after layer N); leaves hidden states in c->x.
+static int run_target_rows(eesd_ctx* c, const int32_t* tok_dev, int M, int pos0) {
+    const bool mfma = pick_mfma(c, M);
+    int rc = launch_embed(c, tok_dev, M);
+    if (rc) return rc;
+    for (int l = 0; l < c->cfg.n_layers; ++l) {
+        rc = run_layer(c, c->layers[l], l, M, pos0, mfma);
+        if (rc) return rc;
+        if (l + 1 == c->cfg.n_draft_layers) {
+            rc = run_ee_kv_fill(c, M, pos0, mfma);
+            if (rc) return rc;
+        }
+    }
+    return EESD_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// paged cache bookkeeping
+// ---------------------------------------------------------------------------------------------
+static int ensure_pages(eesd_ctx* c, int n_tokens) {
+    int need = (n_tokens + c->page_tokens - 1) >> c->page_shift;
+    if (need > c->n_pages) return fail(c, EESD_ERANGE, "KV cache full: %d tokens wanted, max_seq %d", n_tokens, c->cfg.max_seq);
+    int first = c->mapped_pages;
+    while (c->mapped_pages < need) {
+        if (c->free_pages.empty()) return fail(c, EESD_ENOMEM, "KV page pool exhausted");
+        c->h_table[c->mapped_pages++] = c->free_pages.back();
+        c->free_pages.pop_back();
+    }
+    if (c->mapped_pages > first)
+        HIP_TRY(c, hipMemcpyAsync(c->d_table + first, c->h_table + first, sizeof(int32_t) * (c->mapped_pages - first),
+                                  hipMemcpyHostToDevice, c->stream));
+    return EESD_OK;
+}
+
+// pages wholly past n_tokens go back to the pool (callers have synchronised the stream)
+static void release_pages(eesd_ctx* c, int n_tokens) {
+    int keep = (n_tokens + c->page_tokens - 1) >> c->page_shift;
+    while (c->mapped_pages > keep) {
+        --c->mapped_pages;
+        c->free_pages.push_back(c->h_table[c->mapped_pages]);
+        c->h_table[c->mapped_pages] = -1;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// controller (Section 3.3, Algorithm 2)
+// ---------------------------------------------------------------------------------------------
+// theta ~ Beta(a, b).  Integer parameters: the a-th smallest of a+b-1 uniforms (exact, needs
+// comparisons only).  Otherwise the ratio of two Marsaglia-Tsang gamma variates.
+static double gamma_mt(double shape, uint64_t seed, int64_t rnd, int slot, int& sub) {
+    double boost = 1.0;
+    if (shape < 1.0) {
+        boost = pow(uniform53(seed, STREAM_TS_THETA, rnd, slot, sub++), 1.0 / shape);
+        shape += 1.0;
+    }
+    const double d = shape - 1.0 / 3.0, cc = 1.0 / sqrt(9.0 * d);
+    for (;;) {
+        double u1 = uniform53(seed, STREAM_TS_THETA, rnd, slot, sub++), u2 = uniform53(seed, STREAM_TS_THETA, rnd, slot, sub++);
+        double n = sqrt(-2.0 * log(1.0 - u1)) * cos(6.283185307179586 * u2);
+        double v = 1.0 + cc * n;
+        if (v <= 0.0) continue;
+        v = v * v * v;
+        double u = uniform53(seed, STREAM_TS_THETA, rnd, slot, sub++);
+        if (log(1.0 - u) < 0.5 * n * n + d - d * v + d * log(v)) return boost * d * v;
+    }
+}
+
+static double beta_draw(const eesd_ctx* c, int slot) {
+    const double a = c->alpha, b = c->beta;
+    if (a == floor(a) && b == floor(b) && a + b < 1e6) {
+        int ia = (int)a, n = (int)(a + b) - 1;
+        std::vector<double> us(n);
+        for (int j = 0; j < n; ++j) us[j] = uniform53(c->cfg.seed, STREAM_TS_THETA, c->round, slot, j);
+        std::nth_element(us.begin(), us.begin() + (ia - 1), us.end());
+        return us[ia - 1];
+    }
+    int sub = 0;
+    double x = gamma_mt(a, c->cfg.seed, c->round, slot, sub), y = gamma_mt(b, c->cfg.seed, c->round, slot, sub);
+    return x / (x + y);
+}
+
+// K of the coming round.  Every theta of a round is drawn from the posterior the round starts
+// with (Algorithm 2 indexes it by t), so K is known before the first draft step is launched.
+static int draw_k(eesd_ctx* c, int k_max) {
+    if (k_max < 1) k_max = 1;
+    if (c->cfg.ts_mode == EESD_TS_FIXED) return std::min((int)c->cfg.k_cap, k_max);
+    if (c->cfg.ts_mode == EESD_TS_SCHEDULE) {
+        int k = c->cfg.k_cap;
+        if (!c->schedule.empty()) k = c->schedule[std::min<size_t>((size_t)c->sched_round, c->schedule.size() - 1)];
+        ++c->sched_round;
+        return std::max(1, std::min(k, k_max));
+    }
+    int k = 0;
+    for (;;) {
+        ++k;                                  // draft token k
+        if (k >= k_max) return k_max;
+        double theta = beta_draw(c, k);
+        bool chi = uniform53(c->cfg.seed, STREAM_TS_CHI, c->round, k, 0) < theta;
+        if (!chi) return k;
+    }
+}
+
+static void ts_update(eesd_ctx* c, int a, int K) {
+    if (K < 1) return;
+    int r = a;
+    int n = c->cfg.ts_update == 0 ? std::min(a + 1, K) : std::min(a + 2, K);
+    c->alpha += r;
+    c->beta += n - r;
+}
+
+static void finish_stats(eesd_ctx* c) {
+    eesd_stats& s = c->stats;
+    s.v_d = s.drafted ? (double)s.accepted / (double)s.drafted : 0.0;
+    s.r_d = s.generated ? (double)s.accepted / (double)s.generated : 0.0;
+    s.hm = (s.v_d + s.r_d) > 0 ? 2.0 * s.v_d * s.r_d / (s.v_d + s.r_d) * 100.0 : 0.0;
+    s.alpha = c->alpha;
+    s.beta = c->beta;
+}
+
+// ---------------------------------------------------------------------------------------------
+// create / destroy
+// ---------------------------------------------------------------------------------------------
+static const char* k_no_ctx = "no context";
+
+template <typename T>
+static int dev_alloc(eesd_ctx* c, T** p, size_t n) {
+    hipError_t e = hipMalloc((void**)p, n * sizeof(T));
+    if (e != hipSuccess) return fail(c, EESD_ENOMEM, "hipMalloc(%zu bytes): %s", n * sizeof(T), hipGetErrorString(e));
+    return EESD_OK;
+}
+
+extern "C" void eesd_destroy(eesd_ctx* c) {
+    if (!c) return;
+    hipStreamSynchronize(c->stream);
+    void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
+                   c->part_ml, c->rope_cs, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev};
+    for (void* p : dev)
+        if (p) hipFree(p);
+    if (c->h_table) hipHostFree(c->h_table);
+    if (c->h_result) hipHostFree(c->h_result);
+    if (c->h_prompt) hipHostFree(c->h_prompt);
+    for (auto& e : c->ev)
+        if (e) hipEventDestroy(e);
+    delete c;
+}
+
+extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* hip_stream, eesd_ctx** out) {
+    if (!cfg || !w || !out || !w->layers) return EESD_EINVAL;
+    const eesd_config& g = *cfg;
+    if (g.n_layers < 2 || g.n_draft_layers < 1 || g.n_draft_layers >= g.n_layers) return EESD_EINVAL;
+    if (g.d_model < 8 || g.n_heads < 1 || g.n_kv_heads < 1 || g.n_heads % g.n_kv_heads) return EESD_EINVAL;
+    if (g.head_dim != 64 && g.head_dim != 128) return EESD_EINVAL;
+    if (g.d_ff < 8 || g.vocab < 2 || g.max_seq < 2 || g.k_cap < 1 || g.k_cap > ACC_MAX_K) return EESD_EINVAL;
+    if (g.kv_page < 16 || (g.kv_page & (g.kv_page - 1))) return EESD_EINVAL;
+    if (g.dtype != EESD_DTYPE_F32 && g.dtype != EESD_DTYPE_BF16) return EESD_EINVAL;
+    if (!(g.temperature >= 0.0f) || !(g.ts_alpha0 > 0.0) || !(g.ts_beta0 > 0.0)) return EESD_EINVAL;
+    if (g.ts_mode < 0 || g.ts_mode > 2 || g.ts_update < 0 || g.ts_update > 1 || g.gemm_path < 0 || g.gemm_path > 2) return EESD_EINVAL;
+    const int vec = g.dtype == EESD_DTYPE_BF16 ? 8 : 4;
+    const int qd = g.n_heads * g.head_dim;
+    if (g.d_model % vec || g.d_ff % vec || qd % vec || g.vocab % 4 || g.d_ff % 2) return EESD_EINVAL;
+    if (g.dtype == EESD_DTYPE_BF16) {
+        // the MFMA family needs 128-column steps and 32-row blocks
+        if (g.d_model % 128 || g.d_ff % 128 || qd % 128 || g.vocab % 32 || g.d_model % 32 || (g.d_ff % 16)) return EESD_EINVAL;
+    }
+    // whenever the VALU family may see a full block of rows its activations must fit in LDS
+    if ((g.dtype == EESD_DTYPE_F32 || g.gemm_path == EESD_GEMM_VALU) &&
+        valu_lds_bytes(MAX_ROWS, std::max(std::max(g.d_model, g.d_ff), qd)) > 150 * 1024)
+        return EESD_EINVAL;
+    if (valu_lds_bytes(1, std::max(std::max(g.d_model, g.d_ff), qd)) > 150 * 1024) return EESD_EINVAL;
+    const void* ptrs[] = {w->tok_emb, w->final_norm, w->lm_head, w->ee_norm, w->ee_head, w->ee_layer.attn_norm, w->ee_layer.wqkv,
+                          w->ee_layer.wo, w->ee_layer.ffn_norm, w->ee_layer.w_gate_up, w->ee_layer.w_down};
+    for (const void* p : ptrs)
+        if (!p) return EESD_EINVAL;
+    for (int l = 0; l < g.n_layers; ++l) {
+        const eesd_layer_weights& lw = w->layers[l];
+        if (!lw.attn_norm || !lw.wqkv || !lw.wo || !lw.ffn_norm || !lw.w_gate_up || !lw.w_down) return EESD_EINVAL;
+    }
+
+    eesd_ctx* c = new (std::nothrow) eesd_ctx();
+    if (!c) return EESD_ENOMEM;
+    c->cfg = g;
+    c->layers.assign(w->layers, w->layers + g.n_layers);
+    c->w = *w;
+    c->w.layers = c->layers.data();
+    c->stream = (hipStream_t)hip_stream;
+    c->state = ST_CREATED;
+    c->kv_pool = nullptr; c->d_table = nullptr; c->h_table = nullptr;
+    c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = nullptr;
+    c->xb = c->ab = c->actb = nullptr;
+    c->blk_tok = c->prompt_dev = c->result_dev = nullptr;
+    c->h_result = c->h_prompt = nullptr;
+    for (auto& e : c->ev) e = nullptr;
+    c->alpha = g.ts_alpha0; c->beta = g.ts_beta0;
+    c->sched_round = 0; c->round = 0; c->kv_len = 0; c->n_drafted = 0; c->forced_pos = 0;
+    memset(&c->stats, 0, sizeof c->stats);
+
+    int rc = EESD_OK;
+    auto bail = [&](int code) { std::string e = c->err; eesd_destroy(c); (void)e; return code; };
+    if (hipGetDevice(&c->device) != hipSuccess) return bail(EESD_EDEVICE);
+
+    // paged cache
+    c->n_caches = g.n_layers + 1;
+    c->page_tokens = g.kv_page;
+    c->page_shift = 0;
+    while ((1 << c->page_shift) < g.kv_page) ++c->page_shift;
+    c->n_pages = (g.max_seq + g.kv_page - 1) / g.kv_page;
+    c->elem = g.dtype == EESD_DTYPE_BF16 ? 2 : 4;
+    c->page_stride = (long long)c->n_caches * 2 * g.n_kv_heads * g.kv_page * g.head_dim;
+    size_t pool_bytes = (size_t)c->page_stride * c->n_pages * c->elem;
+    if (hipMalloc(&c->kv_pool, pool_bytes) != hipSuccess) return bail(EESD_ENOMEM);
+    if ((rc = dev_alloc(c, &c->d_table, c->n_pages))) return bail(rc);
+    if (hipHostMalloc((void**)&c->h_table, sizeof(int32_t) * c->n_pages, hipHostMallocDefault) != hipSuccess) return bail(EESD_ENOMEM);
+    if (hipHostMalloc((void**)&c->h_result, sizeof(int32_t) * 4, hipHostMallocDefault) != hipSuccess) return bail(EESD_ENOMEM);
+    if (hipHostMalloc((void**)&c->h_prompt, sizeof(int32_t) * g.max_seq, hipHostMallocDefault) != hipSuccess) return bail(EESD_ENOMEM);
+    // physical pages are handed out in reverse order, so logical != physical from the start
+    for (int p = 0; p < c->n_pages; ++p) { c->free_pages.push_back(p); c->h_table[p] = -1; }
+    c->mapped_pages = 0;
+
+    const int d = g.d_model, f = g.d_ff, V = g.vocab;
+    c->max_splits = 64;
+    if ((rc = dev_alloc(c, &c->x, (size_t)MAX_ROWS * d))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->q, (size_t)MAX_ROWS * qd))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->attn, (size_t)MAX_ROWS * qd))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->act, (size_t)MAX_ROWS * f))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->logits, (size_t)MAX_ROWS * V))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->p_rows, (size_t)MAX_ROWS * V))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->q_logits, (size_t)g.k_cap * V))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->q_rows, (size_t)g.k_cap * V))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->part_o, (size_t)MAX_ROWS * g.n_heads * c->max_splits * g.head_dim))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->part_ml, (size_t)MAX_ROWS * g.n_heads * c->max_splits * 2))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->xb, (size_t)MAX_ROWS * d))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->ab, (size_t)MAX_ROWS * qd))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->actb, (size_t)MAX_ROWS * f))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->blk_tok, (size_t)MAX_ROWS + 1))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->prompt_dev, (size_t)g.max_seq))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->result_dev, (size_t)4))) return bail(rc);
+    // rows of the bf16 activation buffers past M are read (and ignored) by the MFMA product
+    hipMemset(c->xb, 0, sizeof(bf16_t) * MAX_ROWS * d);
+    hipMemset(c->ab, 0, sizeof(bf16_t) * MAX_ROWS * qd);
+    hipMemset(c->actb, 0, sizeof(bf16_t) * MAX_ROWS * f);
+    hipMemset(c->d_table, 0, sizeof(int32_t) * c->n_pages);
+    hipMemset(c->kv_pool, 0, pool_bytes);
+
+    // rotary table: cos/sin(pos * base^(-2j/hd)) evaluated in double, stored fp32
+    {
+        const int half = g.head_dim / 2;
+        std::vector<float> cs((size_t)g.max_seq * half * 2);
+        for (int p = 0; p < g.max_seq; ++p)
+            for (int j = 0; j < half; ++j) {
+                double ang = (double)p * pow((double)g.rope_base, -2.0 * j / (double)g.head_dim);
+                cs[((size_t)p * half + j) * 2] = (float)cos(ang);
+                cs[((size_t)p * half + j) * 2 + 1] = (float)sin(ang);
+            }
+        if ((rc = dev_alloc(c, &c->rope_cs, cs.size()))) return bail(rc);
+        if (hipMemcpy(c->rope_cs, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) return bail(EESD_EDEVICE);
+    }
+    for (auto& e : c->ev)
+        if (hipEventCreate(&e) != hipSuccess) return bail(EESD_EDEVICE);
+    if (hipDeviceSynchronize() != hipSuccess) return bail(EESD_EDEVICE);
+    *out = c;
+    return EESD_OK;
+}
+
+extern "C" const char* eesd_last_error(const eesd_ctx* c) { return c ? c->err.c_str() : k_no_ctx; }
+
+extern "C" int eesd_get_stats(const eesd_ctx* c, eesd_stats* out) {
+    if (!c || !out) return EESD_EINVAL;
+    finish_stats(const_cast<eesd_ctx*>(c));
+    *out = c->stats;
+    return EESD_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// the calls of a round
+// ---------------------------------------------------------------------------------------------
+static float inv_temperature(const eesd_ctx* c) { return c->cfg.temperature > 0.f ? 1.0f / c->cfg.temperature : 1.0f; }
+static int greedy(const eesd_ctx* c) { return c->cfg.temperature == 0.f; }
+
+static void reset_sequence(eesd_ctx* c) {
+    release_pages(c, 0);
+    c->kv_len = 0; c->n_drafted = 0; c->round = 0; c->sched_round = 0;
+    c->alpha = c->cfg.ts_alpha0; c->beta = c->cfg.ts_beta0;
+    c->forced.clear(); c->forced_pos = 0;
+    memset(&c->stats, 0, sizeof c->stats);
+}
+
+extern "C" int eesd_prefill(eesd_ctx* c, const int32_t* prompt, int32_t n, int32_t* first_token) {
+    if (!c) return EESD_EINVAL;
+    if (!prompt || !first_token || n < 1) return fail(c, EESD_EINVAL, "prefill: null pointer or empty prompt");
+    const eesd_config& g = c->cfg;
+    if (n + g.k_cap + 1 > g.max_seq) return fail(c, EESD_ERANGE, "prefill: prompt of %d tokens + k_cap + 1 exceeds max_seq %d", n, g.max_seq);
+    for (int i = 0; i < n; ++i)
+        if (prompt[i] < 0 || prompt[i] >= g.vocab) return fail(c, EESD_EINVAL, "prefill: token %d at %d outside [0,%d)", prompt[i], i, g.vocab);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    reset_sequence(c);
+    c->state = ST_CREATED;
+    memcpy(c->h_prompt, prompt, sizeof(int32_t) * n);
+    HIP_TRY(c, hipMemcpyAsync(c->prompt_dev, c->h_prompt, sizeof(int32_t) * n, hipMemcpyHostToDevice, c->stream));
+    int rc = ensure_pages(c, n);
+    if (rc) return rc;
+    int last_m = 0;
+    for (int p0 = 0; p0 < n; p0 += MAX_ROWS) {
+        int m = std::min(MAX_ROWS, n - p0);
+        rc = run_target_rows(c, c->prompt_dev + p0, m, p0);
+        if (rc) return rc;
+        last_m = m;
+    }
+    // logits of the last prompt position only
+    rc = run_head(c, c->w.final_norm, c->w.lm_head, last_m - 1, 1, c->logits, pick_mfma(c, 1));
+    if (rc) return rc;
+    double u = uniform53(g.seed, STREAM_RESAMPLE, 0, 0, 0);
+    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, c->logits, c->p_rows, g.vocab, inv_temperature(c),
+                       greedy(c), u, -1, c->blk_tok);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipMemcpyAsync(c->h_result, c->blk_tok, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->kv_len = n;
+    c->n_drafted = 0;
+    c->round = 1;
+    c->state = ST_READY;
+    *first_token = c->h_result[0];
+    return EESD_OK;
+}
+
+extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
+    if (!c) return EESD_EINVAL;
+    if (c->state != ST_READY) return fail(c, EESD_ESTATE, "draft_step: state is not ready");
+    const eesd_config& g = c->cfg;
+    const int i = c->n_drafted;
+    if (i >= g.k_cap) return fail(c, EESD_ERANGE, "draft_step: k_cap = %d drafts already made", g.k_cap);
+    const int pos = c->kv_len + i;
+    if (pos + 2 > g.max_seq) return fail(c, EESD_ERANGE, "draft_step: position %d does not leave room for verification (max_seq %d)", pos, g.max_seq);
+    int rc = ensure_pages(c, pos + 1);
+    if (rc) return rc;
+    const bool mfma = pick_mfma(c, 1);
+    rc = launch_embed(c, c->blk_tok + i, 1);
+    if (rc) return rc;
+    for (int l = 0; l < g.n_draft_layers; ++l)
+        if ((rc = run_layer(c, c->layers[l], l, 1, pos, mfma))) return rc;
+    if ((rc = run_layer(c, c->w.ee_layer, g.n_layers, 1, pos, mfma))) return rc;
+    float* ql = c->q_logits + (size_t)i * g.vocab;
+    if ((rc = run_head(c, c->w.ee_norm, c->w.ee_head, 0, 1, ql, mfma))) return rc;
+    int forced = -1;
+    if (c->forced_pos < c->forced.size()) forced = c->forced[c->forced_pos++];
+    double u = uniform53(g.seed, STREAM_DRAFT, c->round, i, 0);
+    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, ql, c->q_rows + (size_t)i * g.vocab, g.vocab,
+                       inv_temperature(c), greedy(c), u, forced, c->blk_tok + i + 1);
+    HIP_TRY(c, hipGetLastError());
+    c->n_drafted = i + 1;
+    if (tok_or_null) {
+        HIP_TRY(c, hipMemcpyAsync(c->h_result + 2, c->blk_tok + i + 1, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        *tok_or_null = c->h_result[2];
+    }
+    return EESD_OK;
+}
+
+extern "C" int eesd_verify(eesd_ctx* c) {
+    if (!c) return EESD_EINVAL;
+    if (c->state != ST_READY) return fail(c, EESD_ESTATE, "verify: state is not ready");
+    const eesd_config& g = c->cfg;
+    const int M = c->n_drafted + 1;
+    if (c->kv_len + M > g.max_seq) return fail(c, EESD_ERANGE, "verify: %d rows at %d exceed max_seq %d", M, c->kv_len, g.max_seq);
+    int rc = ensure_pages(c, c->kv_len + M);
+    if (rc) return rc;
+    if ((rc = run_target_rows(c, c->blk_tok, M, c->kv_len))) return rc;
+    if ((rc = run_head(c, c->w.final_norm, c->w.lm_head, 0, M, c->logits, pick_mfma(c, M)))) return rc;
+    c->state = ST_VERIFIED;
+    return EESD_OK;
+}
+
+extern "C" int eesd_accept(eesd_ctx* c, const double* uniforms_or_null, int32_t* n_accepted, int32_t* next_token) {
+    if (!c) return EESD_EINVAL;
+    if (!n_accepted || !next_token) return fail(c, EESD_EINVAL, "accept: null out pointer");
+    if (c->state != ST_VERIFIED) return fail(c, EESD_ESTATE, "accept: nothing verified");
+    const eesd_config& g = c->cfg;
+    const int K = c->n_drafted;
+    AcceptU uu;
+    memset(&uu, 0, sizeof uu);
+    for (int i = 0; i < K; ++i) uu.u[i] = uniforms_or_null ? uniforms_or_null[i] : uniform53(g.seed, STREAM_ACCEPT, c->round, i, 0);
+    uu.u[K] = uniforms_or_null ? uniforms_or_null[K] : uniform53(g.seed, STREAM_RESAMPLE, c->round, 0, 0);
+    for (int i = 0; i <= K; ++i)
+        if (!(uu.u[i] >= 0.0 && uu.u[i] < 1.0)) return fail(c, EESD_EINVAL, "accept: uniform %d outside [0,1)", i);
+    hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, c->logits, c->p_rows, c->q_rows, c->blk_tok + 1, K, g.vocab,
+                       inv_temperature(c), greedy(c), 1, uu, c->result_dev, c->blk_tok);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipMemcpyAsync(c->h_result, c->result_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->last_a = c->h_result[0];
+    c->last_y = c->h_result[1];
+    c->state = ST_ACCEPTED;
+    *n_accepted = c->last_a;
+    *next_token = c->last_y;
+    return EESD_OK;
+}
+
+extern "C" int eesd_rollback(eesd_ctx* c, int32_t n_accepted) {
+    if (!c) return EESD_EINVAL;
+    if (c->state != ST_ACCEPTED) return fail(c, EESD_ESTATE, "rollback: nothing accepted");
+    const int K = c->n_drafted;
+    if (n_accepted < 0 || n_accepted > K) return fail(c, EESD_ERANGE, "rollback: n_accepted %d outside [0,%d]", n_accepted, K);
+    // the stream is idle here: eesd_accept synchronised it
+    c->kv_len += n_accepted + 1;
+    release_pages(c, c->kv_len);
+    // the pending token of the next round is already in blk_tok[0]: the accept kernel stored it
+    ts_update(c, n_accepted, K);
+    c->stats.rounds += 1;
+    c->stats.drafted += K;
+    c->stats.accepted += n_accepted;
+    c->n_drafted = 0;
+    c->round += 1;
+    c->state = ST_READY;
+    return EESD_OK;
+}
+
+extern "C" int eesd_set_draft_schedule(eesd_ctx* c, const int32_t* k_per_round, int32_t n_rounds) {
+    if (!c) return EESD_EINVAL;
+    if (n_rounds < 0 || (n_rounds > 0 && !k_per_round)) return fail(c, EESD_EINVAL, "schedule: null pointer");
+    for (int i = 0; i < n_rounds; ++i)
+        if (k_per_round[i] < 1 || k_per_round[i] > c->cfg.k_cap) return fail(c, EESD_ERANGE, "schedule: K[%d] = %d outside [1,%d]", i, k_per_round[i], c->cfg.k_cap);
+    c->schedule.assign(k_per_round, k_per_round + n_rounds);
+    c->sched_round = 0;
+    return EESD_OK;
+}
+
+extern "C" int eesd_next_draft_len(eesd_ctx* c, int32_t k_max, int32_t* k_out) {
+    if (!c || !k_out) return EESD_EINVAL;
+    *k_out = draw_k(c, std::min((int)k_max, (int)c->cfg.k_cap));
+    return EESD_OK;
+}
+
+static double ms_between(hipEvent_t a, hipEvent_t b) {
+    float ms = 0.f;
+    hipEventElapsedTime(&ms, a, b);
+    return (double)ms;
+}
+
+extern "C" int eesd_generate(eesd_ctx* c, const int32_t* prompt, int32_t n_prompt, int32_t max_new, int32_t* out, int32_t* n_out,
+                             eesd_stats* stats_or_null) {
+    if (!c) return EESD_EINVAL;
+    if (!prompt || !out || !n_out || max_new < 1) return fail(c, EESD_EINVAL, "generate: null pointer or max_new < 1");
+    const eesd_config& g = c->cfg;
+    if (n_prompt + max_new + g.k_cap + 1 > g.max_seq)
+        return fail(c, EESD_ERANGE, "generate: %d prompt + %d new + k_cap + 1 exceeds max_seq %d", n_prompt, max_new, g.max_seq);
+    auto t_begin = std::chrono::steady_clock::now();
+    int32_t tok;
+    int rc = eesd_prefill(c, prompt, n_prompt, &tok);
+    if (rc) return rc;
+    auto t_prefill = std::chrono::steady_clock::now();
+    int n = 0;
+    out[n++] = tok;
+    double ms_d = 0, ms_v = 0, ms_a = 0;
+    std::vector<int32_t> drafts(g.k_cap + 1);
+    while (n < max_new) {
+        const int K = draw_k(c, std::min((int)g.k_cap, max_new - n));
+        HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
+        for (int i = 0; i < K; ++i)
+            if ((rc = eesd_draft_step(c, nullptr))) return rc;
+        HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
+        if ((rc = eesd_verify(c))) return rc;
+        HIP_TRY(c, hipEventRecord(c->ev[2], c->stream));
+        // drafts come back together with the decision: one synchronisation per round
+        HIP_TRY(c, hipMemcpyAsync(c->h_prompt, c->blk_tok + 1, sizeof(int32_t) * K, hipMemcpyDeviceToHost, c->stream));
+        int32_t a, y;
+        if ((rc = eesd_accept(c, nullptr, &a, &y))) return rc;
+        HIP_TRY(c, hipEventRecord(c->ev[3], c->stream));
+        HIP_TRY(c, hipEventSynchronize(c->ev[3]));
+        ms_d += ms_between(c->ev[0], c->ev[1]);
+        ms_v += ms_between(c->ev[1], c->ev[2]);
+        ms_a += ms_between(c->ev[2], c->ev[3]);
+        for (int i = 0; i < a && n < max_new; ++i) out[n++] = c->h_prompt[i];
+        if (n < max_new) out[n++] = y;
+        if ((rc = eesd_rollback(c, a))) return rc;
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    auto t_end = std::chrono::steady_clock::now();
+    c->stats.generated = n;
+    c->stats.ms_draft = ms_d;
+    c->stats.ms_verify = ms_v;
+    c->stats.ms_accept = ms_a;
+    double decode_ms = std::chrono::duration<double, std::milli>(t_end - t_prefill).count();
+    c->stats.ms_other = std::max(0.0, decode_ms - ms_d - ms_v - ms_a);
+    (void)t_begin;
+    finish_stats(c);
+    *n_out = n;
+    if (stats_or_null) *stats_or_null = c->stats;
+    return EESD_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// test and benchmark hooks
+// ---------------------------------------------------------------------------------------------
+extern "C" int eesd_debug_force_drafts(eesd_ctx* c, const int32_t* toks, int32_t n) {
+    if (!c) return EESD_EINVAL;
+    if (n < 0 || (n > 0 && !toks)) return fail(c, EESD_EINVAL, "force_drafts: null pointer");
+    for (int i = 0; i < n; ++i)
+        if (toks[i] < 0 || toks[i] >= c->cfg.vocab) return fail(c, EESD_EINVAL, "force_drafts: token out of range");
+    c->forced.assign(toks, toks + n);
+    c->forced_pos = 0;
+    return EESD_OK;
+}
+
+extern "C" int eesd_debug_force_pending(eesd_ctx* c, int32_t tok) {
+    if (!c) return EESD_EINVAL;
+    if (c->state != ST_READY || c->n_drafted != 0) return fail(c, EESD_ESTATE, "force_pending: state is not ready");
+    if (tok < 0 || tok >= c->cfg.vocab) return fail(c, EESD_EINVAL, "force_pending: token out of range");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->h_result[3] = tok;
+    HIP_TRY(c, hipMemcpyAsync(c->blk_tok, c->h_result + 3, sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return EESD_OK;
+}
+
+template <typename KT>
+__global__ void kv_gather_kernel(KVView kv, bool is_v, int n_tokens, float* __restrict__ out) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    int row = kv.n_kv_heads * kv.head_dim;
+    if (idx >= n_tokens * row) return;
+    int t = idx / row, r = idx - t * row, h = r / kv.head_dim, c = r - h * kv.head_dim;
+    out[idx] = load_as_f32<KT>((const KT*)kv.pool + kv_row_offset(kv, is_v, h, t) + c);
+}
+
+template <typename KT>
+__global__ void kv_pattern_kernel(KVView kv, int n_tokens, unsigned salt) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    int row = kv.n_kv_heads * kv.head_dim;
+    if (idx >= n_tokens * row) return;
+    int t = idx / row, r = idx - t * row, h = r / kv.head_dim, c = r - h * kv.head_dim;
+    unsigned x = (unsigned)idx * 2654435761u + salt;
+    x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
+    float kval = ((float)(x & 0xffff) / 65536.0f - 0.5f) * 2.0f;
+    float vval = ((float)(x >> 16) / 65536.0f - 0.5f) * 2.0f;
+    store_from_f32<KT>((KT*)kv.pool + kv_row_offset(kv, false, h, t) + c, kval);
+    store_from_f32<KT>((KT*)kv.pool + kv_row_offset(kv, true, h, t) + c, vval);
+}
+
+extern "C" int eesd_debug_fill_cache(eesd_ctx* c, int32_t n_tokens, int32_t pending_tok) {
+    if (!c) return EESD_EINVAL;
+    const eesd_config& g = c->cfg;
+    if (n_tokens < 1 || n_tokens + g.k_cap + 1 > g.max_seq) return fail(c, EESD_ERANGE, "fill_cache: %d tokens do not fit", n_tokens);
+    if (pending_tok < 0 || pending_tok >= g.vocab) return fail(c, EESD_EINVAL, "fill_cache: token out of range");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    reset_sequence(c);
+    int rc = ensure_pages(c, n_tokens);
+    if (rc) return rc;
+    int total = n_tokens * g.n_kv_heads * g.head_dim;
+    for (int cache = 0; cache < c->n_caches; ++cache) {
+        KVView v = kv_view(c, cache);
+        if (is_bf16(c)) hipLaunchKernelGGL((kv_pattern_kernel<bf16_t>), dim3((total + 255) / 256), dim3(256), 0, c->stream, v, n_tokens, 977u * cache + 1u);
+        else hipLaunchKernelGGL((kv_pattern_kernel<float>), dim3((total + 255) / 256), dim3(256), 0, c->stream, v, n_tokens, 977u * cache + 1u);
+        HIP_TRY(c, hipGetLastError());
+    }
+    c->h_result[3] = pending_tok;
+    HIP_TRY(c, hipMemcpyAsync(c->blk_tok, c->h_result + 3, sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->kv_len = n_tokens;
+    c->round = 1;
+    c->state = ST_READY;
+    return EESD_OK;
+}
+
+extern "C" int eesd_debug_read(eesd_ctx* c, int what, int index, int32_t n_tokens, void* host_dst, size_t bytes) {
+    if (!c) return EESD_EINVAL;
+    if (!host_dst) return fail(c, EESD_EINVAL, "debug_read: null destination");
+    const eesd_config& g = c->cfg;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const size_t row = sizeof(float) * g.vocab;
+    switch (what) {
+        case EESD_READ_DRAFT_LOGITS:
+        case EESD_READ_DRAFT_PROBS: {
+            if (index < 0 || index >= g.k_cap || bytes < row) return fail(c, EESD_ERANGE, "debug_read: bad draft slot or size");
+            const float* src = (what == EESD_READ_DRAFT_LOGITS ? c->q_logits : c->q_rows) + (size_t)index * g.vocab;
+            HIP_TRY(c, hipMemcpy(host_dst, src, row, hipMemcpyDeviceToHost));
+            return EESD_OK;
+        }
+        case EESD_READ_VERIFY_LOGITS: {
+            if (index < 0 || index >= MAX_ROWS || bytes < row) return fail(c, EESD_ERANGE, "debug_read: bad verify row or size");
+            HIP_TRY(c, hipMemcpy(host_dst, c->logits + (size_t)index * g.vocab, row, hipMemcpyDeviceToHost));
+            return EESD_OK;
+        }
+        case EESD_READ_KV_K:
+        case EESD_READ_KV_V: {
+            if (index < 0 || index >= c->n_caches) return fail(c, EESD_ERANGE, "debug_read: bad cache index");
+            if (n_tokens < 1 || n_tokens > c->mapped_pages * c->page_tokens) return fail(c, EESD_ERANGE, "debug_read: tokens not mapped");
+            size_t total = (size_t)n_tokens * g.n_kv_heads * g.head_dim;
+            if (bytes < total * sizeof(float)) return fail(c, EESD_ERANGE, "debug_read: destination too small");
+            float* tmp = nullptr;
+            if (hipMalloc((void**)&tmp, total * sizeof(float)) != hipSuccess) return fail(c, EESD_ENOMEM, "debug_read: scratch");
+            KVView v = kv_view(c, index);
+            bool is_v = what == EESD_READ_KV_V;
+            if (is_bf16(c)) hipLaunchKernelGGL((kv_gather_kernel<bf16_t>), dim3((total + 255) / 256), dim3(256), 0, c->stream, v, is_v, n_tokens, tmp);
+            else hipLaunchKernelGGL((kv_gather_kernel<float>), dim3((total + 255) / 256), dim3(256), 0, c->stream, v, is_v, n_tokens, tmp);
+            hipError_t e = hipGetLastError();
+            if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+            if (e == hipSuccess) e = hipMemcpy(host_dst, tmp, total * sizeof(float), hipMemcpyDeviceToHost);
+            hipFree(tmp);
+            if (e != hipSuccess) return fail(c, EESD_EDEVICE, "debug_read: %s", hipGetErrorString(e));
+            return EESD_OK;
+        }
+        case EESD_READ_TOKENS: {
+            size_t need = sizeof(int32_t) * (c->n_drafted + 1);
+            if (bytes < need) return fail(c, EESD_ERANGE, "debug_read: destination too small");
+            HIP_TRY(c, hipMemcpy(host_dst, c->blk_tok, need, hipMemcpyDeviceToHost));
+            return EESD_OK;
+        }
+        case EESD_READ_KV_LEN: {
+            if (bytes < sizeof(int32_t)) return fail(c, EESD_ERANGE, "debug_read: destination too small");
+            *(int32_t*)host_dst = c->kv_len;
+            return EESD_OK;
+        }
+        case EESD_READ_PAGE_TABLE: {
+            if (bytes < sizeof(int32_t) * c->n_pages) return fail(c, EESD_ERANGE, "debug_read: destination too small");
+            memcpy(host_dst, c->h_table, sizeof(int32_t) * c->n_pages);
+            return EESD_OK;
+        }
+    }
+    return fail(c, EESD_EINVAL, "debug_read: unknown selector %d", what);
+}
+
+// ---------------------------------------------------------------------------------------------
+// stand-alone kernels
+// ---------------------------------------------------------------------------------------------
+extern "C" int eesd_op_accept(const float* p_rows, const float* q_rows, const int32_t* drafts, const double* uniforms, int32_t K,
+                              int32_t vocab, int32_t greedy_flag, void* hip_stream, int32_t* result) {
+    if (!p_rows || !result || K < 0 || K > ACC_MAX_K || vocab < 2) return EESD_EINVAL;
+    if (K > 0 && !drafts) return EESD_EINVAL;
+    if (!greedy_flag && (!uniforms || (K > 0 && !q_rows))) return EESD_EINVAL;
+    AcceptU uu;
+    memset(&uu, 0, sizeof uu);
+    if (!greedy_flag)
+        for (int i = 0; i <= K; ++i) {
+            if (!(uniforms[i] >= 0.0 && uniforms[i] < 1.0)) return EESD_EINVAL;
+            uu.u[i] = uniforms[i];
+        }
+    hipStream_t st = (hipStream_t)hip_stream;
+    int32_t* d_res = nullptr;
+    if (hipMalloc((void**)&d_res, 2 * sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
+    hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(SMP_THREADS), 0, st, (const float*)nullptr, const_cast<float*>(p_rows), q_rows, drafts, K,
+                       vocab, 1.0f, greedy_flag, 0, uu, d_res, (int32_t*)nullptr);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = hipMemcpy(result, d_res, 2 * sizeof(int32_t), hipMemcpyDeviceToHost);
+    hipFree(d_res);
+    return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
+}
+
+extern "C" int eesd_op_softmax_sample(const float* logits, float* probs, int32_t vocab, float temperature, double u, void* hip_stream,
+                                      int32_t* token) {
+    if (!logits || !token || vocab < 2 || !(temperature >= 0.f) || !(u >= 0.0 && u < 1.0)) return EESD_EINVAL;
+    if (temperature > 0.f && !probs) return EESD_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    int32_t* d_tok = nullptr;
+    if (hipMalloc((void**)&d_tok, sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
+    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), 0, st, logits, probs, vocab, temperature > 0.f ? 1.0f / temperature : 1.0f,
+                       temperature == 0.f, u, -1, d_tok);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = hipMemcpy(token, d_tok, sizeof(int32_t), hipMemcpyDeviceToHost);
+    hipFree(d_tok);
+    return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
+}
+
+extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in, int32_t dtype, int32_t path,
+                            void* hip_stream) {
+    if (!W || !X || !Y || M < 1 || M > MAX_ROWS || out < 2 || in < 8) return EESD_EINVAL;
+    if (dtype != EESD_DTYPE_F32 && dtype != EESD_DTYPE_BF16) return EESD_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool b16 = dtype == EESD_DTYPE_BF16;
+    bool mfma = b16 && (path == EESD_GEMM_MFMA || (path == EESD_GEMM_AUTO && M >= g_mfma_min_m));
+    if (path == EESD_GEMM_MFMA && !b16) return EESD_EINVAL;
+    if (mfma) {
+        if (!mfma_shape_ok(out, in, EPI_PLAIN, 0)) return EESD_EINVAL;
+        // bf16 staging rows of the activations: one buffer per process, grown on demand, kept
+        static bf16_t* xb = nullptr;
+        static size_t xb_elems = 0;
+        const size_t need = (size_t)MAX_ROWS * in;
+        if (need > xb_elems) {
+            if (hipDeviceSynchronize() != hipSuccess) return EESD_EDEVICE;
+            if (xb) hipFree(xb);
+            xb = nullptr; xb_elems = 0;
+            if (hipMalloc((void**)&xb, need * sizeof(bf16_t)) != hipSuccess) return EESD_ENOMEM;
+            if (hipMemset(xb, 0, need * sizeof(bf16_t)) != hipSuccess) return EESD_EDEVICE;
+            xb_elems = need;
+        }
+        hipLaunchKernelGGL(to_bf16_kernel, dim3((in + 255) / 256, M), dim3(256), 0, st, X, in, in, xb, in);
+        hipError_t e = hipGetLastError();
+        if (e == hipSuccess) {
+            GemmP p = gemm_base(W, xb, in, M, out, in);
+            p.Y = Y; p.ldy = out;
+            e = launch_mfma<EPI_PLAIN>(p, st);
+        }
+        return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
+    }
+    if (in % (b16 ? 8 : 4) || out % 2 || valu_lds_bytes(M, in) > 150 * 1024) return EESD_EINVAL;
+    GemmP p = gemm_base(W, X, in, M, out, in);
+    p.Y = Y; p.ldy = out;
+    hipError_t e = launch_valu<EPI_PLAIN>(p, b16, st);
+    return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
+}

@@ -1,0 +1,134 @@
+"""Stand-alone kernels against the oracle: the weight-streaming product, softmax + sampling,
+and the accept / resample decision (bit-exact on identical probability rows and uniforms)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import eesd_oracle as orc
+from gpu_common import TOL_BF16, TOL_F32, rel_err, require_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _pk():
+    import paper_2406_03853_amd as pk
+    return pk
+
+
+def _gemm_case(M, out, inn, dtype, path, seed):
+    pk = _pk()
+    g = torch.Generator().manual_seed(seed)
+    W = (torch.randn(out, inn, generator=g) * 0.05).to(dtype)
+    X = torch.randn(M, inn, generator=g)
+    Y = torch.full((M, out), float("nan"), device="cuda")
+    pk.op_gemm(W.cuda(), X.cuda(), Y, path)
+    torch.cuda.synchronize()
+    want = X.double().numpy() @ W.double().numpy().T
+    return rel_err(Y.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 11, 16])
+@pytest.mark.parametrize("out,inn", [(512, 256), (256, 688), (1376, 256)])
+def test_gemm_valu_fp32(M, out, inn):
+    require_gpu()
+    assert _gemm_case(M, out, inn, torch.float32, _pk().GEMM_VALU, 1) < TOL_F32
+
+
+@pytest.mark.parametrize("M", [1, 2, 4])
+@pytest.mark.parametrize("out,inn", [(1024, 512), (5120, 5120), (320, 13824), (32000, 1024)])
+def test_gemm_valu_bf16(M, out, inn):
+    require_gpu()
+    if M * inn * 4 > 140 * 1024:
+        pytest.skip("activations do not fit in LDS for this family")
+    assert _gemm_case(M, out, inn, torch.bfloat16, _pk().GEMM_VALU, 2) < TOL_F32   # fp32 activations: tight
+
+
+@pytest.mark.parametrize("M", [1, 2, 5, 11, 16])
+@pytest.mark.parametrize("out,inn", [(1024, 512), (5120, 5120), (160, 13824), (32000, 1024), (96, 128)])
+def test_gemm_mfma_bf16(M, out, inn):
+    require_gpu()
+    assert _gemm_case(M, out, inn, torch.bfloat16, _pk().GEMM_MFMA, 3) < TOL_BF16
+
+
+@pytest.mark.parametrize("t,nw", [(1, 1), (1, 4), (1, 16), (2, 2), (2, 8)])
+def test_gemm_mfma_launch_shapes(t, nw):
+    require_gpu()
+    pk = _pk()
+    try:
+        pk.set_tunable("mfma_t", t)
+        pk.set_tunable("mfma_nw", nw)
+        assert _gemm_case(7, 2048, 2048, torch.bfloat16, pk.GEMM_MFMA, 4) < TOL_BF16
+    finally:
+        pk.set_tunable("mfma_t", 0)
+        pk.set_tunable("mfma_nw", 0)
+
+
+@pytest.mark.parametrize("V", [512, 1000, 32000])
+def test_softmax_sample_bit_exact_tokens(V):
+    require_gpu()
+    pk = _pk()
+    logits = si.make_logit_rows(24, V, seed=V)
+    us = si.make_uniforms(24, seed=V + 1)
+    for i in range(24):
+        T = [1.0, 0.7, 0.0][i % 3]
+        lg = torch.from_numpy(logits[i]).cuda()
+        probs = torch.zeros(V, device="cuda")
+        tok = pk.op_softmax_sample(lg, probs, T, float(us[i]))
+        if T == 0.0:
+            assert tok == orc.argmax_lowest(logits[i])
+            continue
+        p_gpu = probs.cpu().numpy()
+        p_ref = orc.softmax(logits[i].astype(np.float64) / T)
+        assert np.max(np.abs(p_gpu - p_ref)) < 2e-6 * np.max(p_ref)
+        # the decision is defined on the fp32 row: same row + same uniform => same token
+        assert tok == orc.decide_sample(p_gpu, float(us[i]))
+
+
+def test_argmax_ties_lowest_index():
+    require_gpu()
+    pk = _pk()
+    row = np.zeros(5000, np.float32)
+    row[[4100, 77, 2500]] = 3.0
+    assert pk.op_softmax_sample(torch.from_numpy(row).cuda(), None, 0.0, 0.0) == 77
+
+
+@pytest.mark.parametrize("V", [512, 32000])
+@pytest.mark.parametrize("K", [0, 1, 3, 10, 15])
+def test_accept_decision_bit_exact(V, K):
+    require_gpu()
+    pk = _pk()
+    mism = 0
+    for s in range(12):
+        p = si.make_prob_rows(K + 1, V, seed=100 * K + s, zero_frac=0.1 if s % 3 == 0 else 0.0)
+        # q close to p so that accept / reject both occur along the block
+        q = p[:K] * np.exp(0.6 * np.random.default_rng(s).standard_normal((K, V))).astype(np.float32) if K else np.zeros((0, V), np.float32)
+        if K:
+            q = (q / q.sum(axis=1, keepdims=True)).astype(np.float32)
+        drafts = np.array([orc.decide_sample(q[i], u) for i, u in enumerate(si.make_uniforms(K, seed=7 * s))], np.int32)
+        us = si.make_uniforms(K + 1, seed=31 * s + K)
+        want = orc.decide_accept(p, q if K else None, drafts, us[:K], us[K], greedy=False)
+        qd = torch.from_numpy(q).cuda() if K else None
+        got = pk.op_accept(torch.from_numpy(p).cuda(), qd, torch.from_numpy(drafts).cuda(), us, greedy=False)
+        assert got == want, (s, got, want)
+        mism += want[0] < K
+    if K >= 3:
+        assert 0 < mism      # rejections did happen
+
+
+def test_accept_special_rows():
+    require_gpu()
+    pk = _pk()
+    V = 2048
+    p = si.make_prob_rows(4, V, seed=5)
+    drafts = torch.tensor([3, 900, 2047], dtype=torch.int32, device="cuda")
+    # q == p: all accepted, bonus from the last row
+    us = si.make_uniforms(4, 9)
+    a, y = pk.op_accept(torch.from_numpy(p).cuda(), torch.from_numpy(p[:3].copy()).cuda(), drafts, us, greedy=False)
+    assert (a, y) == (3, orc.decide_sample(p[3], us[3]))
+    # greedy on logits
+    lg = si.make_logit_rows(4, V, seed=6)
+    tops = lg.argmax(axis=1)
+    d = torch.tensor([tops[0], tops[1], (tops[2] + 1) % V], dtype=torch.int32, device="cuda")
+    assert pk.op_accept(torch.from_numpy(lg).cuda(), None, d, None, greedy=True) == (2, int(tops[2]))
+    assert pk.op_accept(torch.from_numpy(lg).cuda(), None, d, None, greedy=True) == orc.decide_accept(lg, None, d.cpu().numpy(), None, None, True)
