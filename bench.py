@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the EESD hot path on one MI355X.
+
+A *step* is one whole `eesd_generate` call: prefill of the prompt, then decoding rounds
+(K draft steps chosen by the Beta-posterior controller, one (K+1)-token verification,
+accept / resample, KV rollback) until `max_new` tokens exist.  Inputs (random bf16 weights
+of the named LLaMA-2 shape, a uniform-random prompt) are resident in HBM before the timed
+region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 70b|13b|13b-long|tiny]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOADS = {
+    # name: (shape key, weight seed, prompt tokens, new tokens, k_cap)
+    "70b": ("LLAMA70B", 2, 512, 256, 10),
+    "13b": ("LLAMA13B", 1, 256, 256, 10),
+    "13b-long": ("LLAMA13B", 1, 3840, 256, 10),
+    "tiny": ("TINY", 0, 32, 64, 5),
+}
+HBM_PEAK_GBS = 8000.0
+
+
+def pass_bytes(shape, n_layers_run, with_head, kv_tokens, si):
+    """Algorithmic bytes of one pass: every weight of the layers it runs once, its LM head,
+    and the cached keys/values it attends over."""
+    b = n_layers_run * si.layer_bytes(shape) + (si.head_bytes(shape) if with_head else 0)
+    b += n_layers_run * kv_tokens * si.kv_bytes_per_token_layer(shape)
+    return b
+
+
+def cpu_baseline(w_gpu, shape, temperature, mean_k, mean_commit, si):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample: the same
+    weights at depth L=2, N=1, a few rounds; per-parameter time scaled to the full depth."""
+    import numpy as np
+    from oracle import eesd_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    sh = si.reduced_depth(shape, 2, 1)
+    sub = dict(shape=sh, tok_emb=w_gpu["tok_emb"], layers=w_gpu["layers"][:2], final_norm=w_gpu["final_norm"],
+               lm_head=w_gpu["lm_head"], ee_layer=w_gpu["ee_layer"], ee_norm=w_gpu["ee_norm"], ee_head=w_gpu["ee_head"])
+    w = si.weights_to_numpy(sub)
+    o = orc.OracleEESD(w, max_seq=64, temperature=temperature, seed=0, k_cap=4)
+    o.prefill(si.make_prompt(4, sh["vocab"], 0))
+    t_d, t_v, rounds = 0.0, 0.0, 0
+    t_start = time.perf_counter()
+    while rounds < 2 or (time.perf_counter() - t_start < 12.0 and rounds < 6):
+        t0 = time.perf_counter()
+        o.draft_step()
+        t1 = time.perf_counter()
+        o.verify()
+        t2 = time.perf_counter()
+        a, y = o.accept()
+        o.rollback(a, y)
+        t_d += t1 - t0
+        t_v += t2 - t1
+        rounds += 1
+    p_layer, p_head = si.layer_param_count(sh), sh["vocab"] * sh["d_model"]
+    p_kv = 2 * sh["n_kv_heads"] * sh["head_dim"] * sh["d_model"]
+    c1 = (t_d / rounds) / (2 * p_layer + p_head)              # seconds per parameter, one row
+    c2 = (t_v / rounds) / (2 * p_layer + p_kv + p_head)       # seconds per parameter, two rows
+    L, N = shape["n_layers"], shape["n_draft_layers"]
+    t_draft_full = c1 * ((N + 1) * p_layer + p_head)
+    t_verify_full = c2 * (L * p_layer + p_kv + p_head)
+    tok_s = mean_commit / (mean_k * t_draft_full + t_verify_full)
+    return dict(value=tok_s, unit="tokens/s", cores=int(cores), kind="oracle",
+                sample=f"{rounds} rounds (1 draft step + 1 two-row verify) of the fp64 numpy oracle on the first 2 layers "
+                       f"+ early-exit layer + heads of the same weights; seconds per parameter scaled to L={L}, N={N} "
+                       f"with the GPU run's mean K={mean_k:.2f} and {mean_commit:.2f} tokens per round",
+                draft_step_s=t_draft_full, verify_s=t_verify_full)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="70b", choices=sorted(WORKLOADS))
+    ap.add_argument("--temperature", type=float, default=1.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (batch-1 decoding does not shard across GPUs here); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth_inputs as si
+    import paper_2406_03853_amd as pk
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    pk.lib()  # fails loudly if libeesd.so is not built
+    shape_key, wseed, n_prompt, max_new, k_cap = WORKLOADS[args.workload]
+    shape = getattr(si, shape_key)
+    t0 = time.perf_counter()
+    w = si.make_weights(shape, seed=wseed, device="cuda")
+    torch.cuda.synchronize()
+    t_weights = time.perf_counter() - t0
+    max_seq = n_prompt + max_new + k_cap + 2
+    max_seq = (max_seq + 63) // 64 * 64
+    ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64)
+    prompt = si.make_prompt(n_prompt, shape["vocab"], 0)
+
+    for _ in range(args.warmup):
+        ctx.generate(prompt, max_new)
+    torch.cuda.synchronize()
+    bf16 = shape["dtype"] == "bf16"
+    # dominant kernel: the gate/up product of the verify pass (MFMA family on bf16, VALU on fp32)
+    ctx.profile_begin(1 if bf16 else 0, 2, shape["d_model"])
+    t0 = time.perf_counter()
+    stats = []
+    for _ in range(args.steps):
+        _, st = ctx.generate(prompt, max_new)
+        stats.append(st)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_launch, ms_kernel = ctx.profile_end()
+
+    st = stats[-1]
+    rounds = sum(s.rounds for s in stats)
+    mean_k = sum(s.drafted for s in stats) / max(1, rounds)
+    mean_commit = sum(s.accepted + s.rounds for s in stats) / max(1, rounds)
+    ms_draft = sum(s.ms_draft for s in stats) / max(1, sum(s.drafted for s in stats))
+    ms_verify = sum(s.ms_verify for s in stats) / max(1, rounds)
+    ms_accept = sum(s.ms_accept for s in stats) / max(1, rounds)
+    N, L = shape["n_draft_layers"], shape["n_layers"]
+    ctx_mid = n_prompt + max_new // 2
+    b_draft = pass_bytes(shape, N + 1, True, ctx_mid, si)
+    b_verify = pass_bytes(shape, L, True, ctx_mid, si) + 2 * shape["n_kv_heads"] * shape["head_dim"] * shape["d_model"] * (2 if bf16 else 4)
+    esz = 2 if bf16 else 4
+    kernel_bytes = 2 * shape["d_ff"] * shape["d_model"] * esz          # weights of one gate/up product
+    avg_kernel_s = (ms_kernel / max(1, n_launch)) * 1e-3
+    achieved = kernel_bytes / avg_kernel_s / 1e9 if n_launch else 0.0
+
+    out = {
+        "metric": "decoded tokens/s bs=1 (70B-shape bf16); HBM GB/s of draft+verify passes",
+        "value": args.steps * max_new / dt,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"full EESD generation, {shape['name']} (L={L}, N={N}), random weights seed {wseed}, "
+                               f"prompt {n_prompt} uniform ids, {max_new} new tokens, Beta-TS K cap {k_cap}, "
+                               f"temperature {args.temperature:g}, batch 1",
+                   "prefill": "included in every step (16-row blocks through the verify path)"},
+        "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<SWIGLU> (gate/up product of verify and prefill blocks)" if bf16
+                     else "gemm_valu_kernel<SWIGLU>",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "launches_timed": n_launch, "avg_kernel_us": avg_kernel_s * 1e6,
+                     "bytes_per_launch": kernel_bytes},
+        "passes": {"draft_step_ms": ms_draft, "verify_ms": ms_verify, "accept_ms": ms_accept,
+                   "draft_step_GBps": b_draft / (ms_draft * 1e-3) / 1e9 if ms_draft else None,
+                   "verify_GBps": b_verify / (ms_verify * 1e-3) / 1e9 if ms_verify else None,
+                   "draft_step_bytes": b_draft, "verify_bytes": b_verify,
+                   "mean_K": mean_k, "tokens_per_round": mean_commit, "v_d": st.v_d, "r_d": st.r_d, "hm": st.hm,
+                   "ts_alpha": st.alpha, "ts_beta": st.beta, "weight_init_s": t_weights},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, shape, args.temperature, mean_k, mean_commit, si)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -201,6 +201,14 @@ int eesd_debug_force_pending(eesd_ctx* ctx, int32_t tok);
  * kv_len = n_tokens, pending = tok: a stand-in for a prefilled cache in micro-benchmarks. */
 int eesd_debug_fill_cache(eesd_ctx* ctx, int32_t n_tokens, int32_t pending_tok);
 
+/* Times one class of weight-streaming product launches with HIP events on the context's
+ * stream: family 0 = VALU (M = 1 / fp32), 1 = MFMA (bf16, M >= 2); epilogue_kind 0 = LM head,
+ * 1 = residual (attention output and FFN down), 2 = SwiGLU (gate/up), 3 = QKV; in_dim filters
+ * on the reduction length (0 = any).  _end synchronises and returns launches seen and their
+ * summed duration (at most 8192 launches are timed). */
+int eesd_debug_profile_begin(eesd_ctx* ctx, int32_t family, int32_t epilogue_kind, int32_t in_dim);
+int eesd_debug_profile_end(eesd_ctx* ctx, int32_t* n_launches, double* total_ms);
+
 /* Launch-shape knobs for benchmark sweeps (process-wide; 0 restores the built-in heuristic):
  * "valu_nw", "valu_tpw", "valu_rp", "mfma_t", "mfma_nw", "attn_split", "mfma_min_m". */
 int eesd_set_tunable(const char* name, int value);

@@ -75,7 +75,7 @@ _LIB = None
 EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_rollback",
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
-           "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
+           "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
 
 
 def lib() -> C.CDLL:
@@ -107,6 +107,8 @@ def lib() -> C.CDLL:
     L.eesd_debug_force_pending.argtypes = [VP, I32]
     L.eesd_debug_fill_cache.argtypes = [VP, I32, I32]
     L.eesd_set_tunable.argtypes = [C.c_char_p, C.c_int]
+    L.eesd_debug_profile_begin.argtypes = [VP, I32, I32, I32]
+    L.eesd_debug_profile_end.argtypes = [VP, P(I32), P(C.c_double)]
     L.eesd_op_accept.argtypes = [VP, VP, VP, P(C.c_double), I32, I32, I32, VP, P(I32)]
     L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
     L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, VP]
@@ -233,6 +235,14 @@ class EESD:
 
     def fill_cache(self, n_tokens: int, pending: int = 1) -> None:
         self._ck(lib().eesd_debug_fill_cache(self._h, int(n_tokens), int(pending)))
+
+    def profile_begin(self, family: int, epilogue_kind: int, in_dim: int = 0) -> None:
+        self._ck(lib().eesd_debug_profile_begin(self._h, family, epilogue_kind, in_dim))
+
+    def profile_end(self):
+        n, ms = C.c_int32(), C.c_double()
+        self._ck(lib().eesd_debug_profile_end(self._h, C.byref(n), C.byref(ms)))
+        return n.value, ms.value
 
     def _read(self, what: int, index: int, n_tokens: int, arr: np.ndarray) -> np.ndarray:
         self._ck(lib().eesd_debug_read(self._h, what, index, n_tokens, arr.ctypes.data_as(C.c_void_p), arr.nbytes))

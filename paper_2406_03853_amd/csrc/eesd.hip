@@ -106,6 +106,11 @@ struct eesd_ctx {
     int32_t *h_result, *h_prompt;  // pinned
     int max_splits;
     hipEvent_t ev[4];
+
+    // per-kernel timing of one class of product launches (benchmark hook)
+    int prof_family, prof_epi, prof_in;   // family: -1 off, 0 VALU, 1 MFMA
+    std::vector<hipEvent_t> prof_ev;      // start/stop pairs
+    size_t prof_used;
 };
 
 static int fail(eesd_ctx* c, int code, const char* fmt, ...) {
@@ -199,34 +204,33 @@ static hipError_t launch_valu(const GemmP& p, bool bf16, hipStream_t st) {
     return bf16 ? launch_valu_m<bf16_t, EPI>(p, st) : launch_valu_m<float, EPI>(p, st);
 }
 
+template <int EPI, int T>
+static hipError_t launch_mfma_t(const GemmP& p, int n_blocks, int nw, hipStream_t st) {
+    size_t lds = (size_t)nw * 2 * T * 64 * 16;  // split-K reduction
+    auto fn = gemm_mfma_kernel<EPI, T>;
+    hipError_t e = allow_lds((const void*)fn, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fn, dim3(n_blocks), dim3(nw * 64), lds, st, p);
+    return hipGetLastError();
+}
+
 template <int EPI>
 static hipError_t launch_mfma(const GemmP& p, hipStream_t st) {
     int unit = (EPI == EPI_QKV) ? p.head_dim / 2 : p.out_rows / 2;
     // T tiles of 16 rows per block half: 16*T must divide `unit`
-    int T = g_mfma_t ? g_mfma_t : ((p.out_rows / 64) >= 2048 ? 2 : 1);
+    int T = g_mfma_t ? g_mfma_t : 1;
     if (unit % (16 * T)) T = 1;
     int n_blocks = p.out_rows / (32 * T);
     int steps = p.in_dim / 128;
     int nw = g_mfma_nw;
     if (!nw) {
+        // about 1-2 thousand waves over the chip, at least two 128-column steps per wave
         nw = 1;
-        while (nw * 2 <= 16 && nw * 2 * 4 <= steps) nw *= 2;
+        while (nw < 8 && n_blocks * nw < 1024 && steps / (nw * 2) >= 2) nw *= 2;
     }
     nw = std::max(nw, T);
     nw = std::min(nw, std::max(steps, T));
-    size_t lds = (size_t)nw * 2 * T * 64 * 16;
-    if (T == 2) {
-        auto fn = gemm_mfma_kernel<EPI, 2>;
-        hipError_t e = allow_lds((const void*)fn, lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(fn, dim3(n_blocks), dim3(nw * 64), lds, st, p);
-    } else {
-        auto fn = gemm_mfma_kernel<EPI, 1>;
-        hipError_t e = allow_lds((const void*)fn, lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(fn, dim3(n_blocks), dim3(nw * 64), lds, st, p);
-    }
-    return hipGetLastError();
+    return T == 2 ? launch_mfma_t<EPI, 2>(p, n_blocks, nw, st) : launch_mfma_t<EPI, 1>(p, n_blocks, nw, st);
 }
 
 static bool mfma_shape_ok(int out, int in, int epi, int head_dim) {
@@ -242,6 +246,28 @@ static bool pick_mfma(const eesd_ctx* c, int M) {
     if (c->cfg.gemm_path == EESD_GEMM_VALU) return false;
     if (c->cfg.gemm_path == EESD_GEMM_MFMA) return true;
     return M >= g_mfma_min_m;
+}
+
+#define PROF_MAX_PAIRS 8192
+
+template <int EPI>
+static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p) {
+    bool prof = c->prof_family == (mfma ? 1 : 0) && c->prof_epi == EPI && (c->prof_in == 0 || c->prof_in == p.in_dim) &&
+                c->prof_used < PROF_MAX_PAIRS;
+    if (prof) {
+        while (c->prof_ev.size() < 2 * (c->prof_used + 1)) {
+            hipEvent_t e;
+            HIP_TRY(c, hipEventCreate(&e));
+            c->prof_ev.push_back(e);
+        }
+        HIP_TRY(c, hipEventRecord(c->prof_ev[2 * c->prof_used], c->stream));
+    }
+    HIP_TRY(c, mfma ? launch_mfma<EPI>(p, c->stream) : launch_valu<EPI>(p, is_bf16(c), c->stream));
+    if (prof) {
+        HIP_TRY(c, hipEventRecord(c->prof_ev[2 * c->prof_used + 1], c->stream));
+        ++c->prof_used;
+    }
+    return EESD_OK;
 }
 
 static GemmP gemm_base(const void* W, const void* X, int ldx, int M, int out, int in) {
@@ -319,43 +345,43 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
     const eesd_config& g = c->cfg;
     const int d = g.d_model, hd = g.head_dim, qd = g.n_heads * hd, f = g.d_ff;
     const int qkv_rows = (g.n_heads + 2 * g.n_kv_heads) * hd;
-    const bool b16 = is_bf16(c);
+    int rc;
     if (mfma) {
-        int rc = launch_rmsnorm_bf16(c, c->x, M, lw.attn_norm, c->xb, d);
+        rc = launch_rmsnorm_bf16(c, c->x, M, lw.attn_norm, c->xb, d);
         if (rc) return rc;
         GemmP p = gemm_base(lw.wqkv, c->xb, d, M, qkv_rows, d);
         fill_qkv(c, p, cache, pos0, 0);
-        HIP_TRY(c, launch_mfma<EPI_QKV>(p, c->stream));
+        if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
         rc = launch_attention(c, cache, M, pos0, true);
         if (rc) return rc;
         p = gemm_base(lw.wo, c->ab, qd, M, d, qd);
         p.Y = c->x; p.ldy = d;
-        HIP_TRY(c, launch_mfma<EPI_RESID>(p, c->stream));
+        if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
         rc = launch_rmsnorm_bf16(c, c->x, M, lw.ffn_norm, c->xb, d);
         if (rc) return rc;
         p = gemm_base(lw.w_gate_up, c->xb, d, M, 2 * f, d);
         p.Y = c->actb; p.ldy = f; p.y_bf16 = 1;
-        HIP_TRY(c, launch_mfma<EPI_SWIGLU>(p, c->stream));
+        if ((rc = gemm_launch<EPI_SWIGLU>(c, true, p))) return rc;
         p = gemm_base(lw.w_down, c->actb, f, M, d, f);
         p.Y = c->x; p.ldy = d;
-        HIP_TRY(c, launch_mfma<EPI_RESID>(p, c->stream));
+        if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
     } else {
         GemmP p = gemm_base(lw.wqkv, c->x, d, M, qkv_rows, d);
         p.gain = lw.attn_norm; p.eps = g.rms_eps;
         fill_qkv(c, p, cache, pos0, 0);
-        HIP_TRY(c, launch_valu<EPI_QKV>(p, b16, c->stream));
-        int rc = launch_attention(c, cache, M, pos0, false);
+        if ((rc = gemm_launch<EPI_QKV>(c, false, p))) return rc;
+        rc = launch_attention(c, cache, M, pos0, false);
         if (rc) return rc;
         p = gemm_base(lw.wo, c->attn, qd, M, d, qd);
         p.Y = c->x; p.ldy = d;
-        HIP_TRY(c, launch_valu<EPI_RESID>(p, b16, c->stream));
+        if ((rc = gemm_launch<EPI_RESID>(c, false, p))) return rc;
         p = gemm_base(lw.w_gate_up, c->x, d, M, 2 * f, d);
         p.gain = lw.ffn_norm; p.eps = g.rms_eps;
         p.Y = c->act; p.ldy = f; p.y_bf16 = 0;
-        HIP_TRY(c, launch_valu<EPI_SWIGLU>(p, b16, c->stream));
+        if ((rc = gemm_launch<EPI_SWIGLU>(c, false, p))) return rc;
         p = gemm_base(lw.w_down, c->act, f, M, d, f);
         p.Y = c->x; p.ldy = d;
-        HIP_TRY(c, launch_valu<EPI_RESID>(p, b16, c->stream));
+        if ((rc = gemm_launch<EPI_RESID>(c, false, p))) return rc;
     }
     return EESD_OK;
 }
@@ -368,17 +394,18 @@ static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
     const size_t esz = is_bf16(c) ? 2 : 4;
     const char* wkv = (const char*)c->w.ee_layer.wqkv + (size_t)g.n_heads * hd * d * esz;
     const int rows = 2 * g.n_kv_heads * hd;
+    int rc;
     if (mfma) {
-        int rc = launch_rmsnorm_bf16(c, c->x, M, c->w.ee_layer.attn_norm, c->xb, d);
+        rc = launch_rmsnorm_bf16(c, c->x, M, c->w.ee_layer.attn_norm, c->xb, d);
         if (rc) return rc;
         GemmP p = gemm_base(wkv, c->xb, d, M, rows, d);
         fill_qkv(c, p, g.n_layers, pos0, g.n_heads);
-        HIP_TRY(c, launch_mfma<EPI_QKV>(p, c->stream));
+        if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
     } else {
         GemmP p = gemm_base(wkv, c->x, d, M, rows, d);
         p.gain = c->w.ee_layer.attn_norm; p.eps = g.rms_eps;
         fill_qkv(c, p, g.n_layers, pos0, g.n_heads);
-        HIP_TRY(c, launch_valu<EPI_QKV>(p, is_bf16(c), c->stream));
+        if ((rc = gemm_launch<EPI_QKV>(c, false, p))) return rc;
     }
     return EESD_OK;
 }
@@ -388,17 +415,18 @@ static int run_head(eesd_ctx* c, const void* norm, const void* head, int x0, int
     const eesd_config& g = c->cfg;
     const int d = g.d_model;
     const float* xr = c->x + (size_t)x0 * d;
+    int rc;
     if (mfma) {
-        int rc = launch_rmsnorm_bf16(c, xr, M, norm, c->xb, d);
+        rc = launch_rmsnorm_bf16(c, xr, M, norm, c->xb, d);
         if (rc) return rc;
         GemmP p = gemm_base(head, c->xb, d, M, g.vocab, d);
         p.Y = logits; p.ldy = g.vocab;
-        HIP_TRY(c, launch_mfma<EPI_PLAIN>(p, c->stream));
+        if ((rc = gemm_launch<EPI_PLAIN>(c, true, p))) return rc;
     } else {
         GemmP p = gemm_base(head, xr, d, M, g.vocab, d);
         p.gain = norm; p.eps = g.rms_eps;
         p.Y = logits; p.ldy = g.vocab;
-        HIP_TRY(c, launch_valu<EPI_PLAIN>(p, is_bf16(c), c->stream));
+        if ((rc = gemm_launch<EPI_PLAIN>(c, false, p))) return rc;
     }
     return EESD_OK;
 }
@@ -556,6 +584,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (c->h_prompt) hipHostFree(c->h_prompt);
     for (auto& e : c->ev)
         if (e) hipEventDestroy(e);
+    for (auto& e : c->prof_ev) hipEventDestroy(e);
     delete c;
 }
 
@@ -607,6 +636,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     for (auto& e : c->ev) e = nullptr;
     c->alpha = g.ts_alpha0; c->beta = g.ts_beta0;
     c->sched_round = 0; c->round = 0; c->kv_len = 0; c->n_drafted = 0; c->forced_pos = 0;
+    c->prof_family = -1; c->prof_epi = 0; c->prof_in = 0; c->prof_used = 0;
     memset(&c->stats, 0, sizeof c->stats);
 
     int rc = EESD_OK;
@@ -1030,6 +1060,26 @@ extern "C" int eesd_debug_read(eesd_ctx* c, int what, int index, int32_t n_token
         }
     }
     return fail(c, EESD_EINVAL, "debug_read: unknown selector %d", what);
+}
+
+extern "C" int eesd_debug_profile_begin(eesd_ctx* c, int32_t family, int32_t epilogue_kind, int32_t in_dim) {
+    if (!c) return EESD_EINVAL;
+    if (family < 0 || family > 1 || epilogue_kind < 0 || epilogue_kind > 3 || in_dim < 0) return fail(c, EESD_EINVAL, "profile_begin: bad selector");
+    c->prof_family = family; c->prof_epi = epilogue_kind; c->prof_in = in_dim; c->prof_used = 0;
+    return EESD_OK;
+}
+
+extern "C" int eesd_debug_profile_end(eesd_ctx* c, int32_t* n_launches, double* total_ms) {
+    if (!c) return EESD_EINVAL;
+    if (!n_launches || !total_ms) return fail(c, EESD_EINVAL, "profile_end: null pointer");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    double ms = 0.0;
+    for (size_t i = 0; i < c->prof_used; ++i) ms += ms_between(c->prof_ev[2 * i], c->prof_ev[2 * i + 1]);
+    *n_launches = (int32_t)c->prof_used;
+    *total_ms = ms;
+    c->prof_family = -1;
+    c->prof_used = 0;
+    return EESD_OK;
 }
 
 // ---------------------------------------------------------------------------------------------

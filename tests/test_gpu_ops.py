@@ -59,6 +59,7 @@ def test_gemm_mfma_launch_shapes(t, nw):
         pk.set_tunable("mfma_t", t)
         pk.set_tunable("mfma_nw", nw)
         assert _gemm_case(7, 2048, 2048, torch.bfloat16, pk.GEMM_MFMA, 4) < TOL_BF16
+        assert _gemm_case(16, 192, 1280, torch.bfloat16, pk.GEMM_MFMA, 5) < TOL_BF16
     finally:
         pk.set_tunable("mfma_t", 0)
         pk.set_tunable("mfma_nw", 0)
