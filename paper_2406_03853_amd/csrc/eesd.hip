@@ -143,6 +143,7 @@ static KVView kv_view(const eesd_ctx* c, int cache) {
     v.page_shift = c->page_shift;
     v.n_kv_heads = c->cfg.n_kv_heads;
     v.head_dim = c->cfg.head_dim;
+    v.v_transposed = is_bf16(c) ? 1 : 0;
     return v;
 }
 
@@ -170,7 +171,7 @@ static hipError_t launch_valu_t(const GemmP& p, hipStream_t st) {
     int n_tasks = (p.out_rows / 2) / RP;
     size_t lds = ((size_t)MT * p.in_dim + MT) * sizeof(float);
     if (lds > 150 * 1024) return hipErrorInvalidValue;
-    int nw = g_valu_nw ? g_valu_nw : (lds > 40 * 1024 ? 16 : 4);
+    int nw = g_valu_nw ? g_valu_nw : ((lds > 40 * 1024 || sizeof(WT) == 2) ? 16 : 4);
     int tpw = g_valu_tpw ? g_valu_tpw : std::max(1, std::min(8, n_tasks / 8192));
     int grid = (n_tasks + nw * tpw - 1) / (nw * tpw);
     auto fn = gemm_valu_kernel<WT, MT, EPI, RP>;
@@ -279,26 +280,29 @@ static GemmP gemm_base(const void* W, const void* X, int ldx, int M, int out, in
 
 static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf16) {
     const eesd_config& g = c->cfg;
+    const bool kb = is_bf16(c);
     AttnP a;
     memset(&a, 0, sizeof a);
     a.Q = c->q;
     a.kv = kv_view(c, cache);
     a.M = M; a.pos0 = pos0;
     a.n_heads = g.n_heads; a.n_kv_heads = g.n_kv_heads; a.head_dim = g.head_dim;
-    int n_keys = pos0 + M;
-    int group = g.n_heads / g.n_kv_heads;
-    int qblocks = (M * group + ATT_QG - 1) / ATT_QG;
-    // enough workgroups to cover the chip, splits of at least 2 tiles
+    const int n_keys = pos0 + M;
+    const int group = g.n_heads / g.n_kv_heads;
+    // bf16: one wave per 16 query rows, all of a KV head's rows in one workgroup; fp32: 16 rows per workgroup
+    const int qtiles = (M * group + 15) / 16;
+    const int tile = kb ? 32 : ATT_TT;          // keys per inner step
     int split_len = g_attn_split;
     if (!split_len) {
-        int want = std::max(1, 1024 / std::max(1, g.n_kv_heads * qblocks));
+        // enough waves to cover the chip, at least two steps per split when the cache is long
+        int want = std::max(1, 2048 / std::max(1, g.n_kv_heads * qtiles));
         split_len = (n_keys + want - 1) / want;
-        split_len = std::max(2 * ATT_TT, (split_len + ATT_TT - 1) / ATT_TT * ATT_TT);
+        split_len = std::max(kb ? 64 : 2 * ATT_TT, split_len);
     }
+    split_len = (split_len + tile - 1) / tile * tile;
     int n_splits = (n_keys + split_len - 1) / split_len;
     if (n_splits > c->max_splits) {
-        n_splits = c->max_splits;
-        split_len = ((n_keys + n_splits - 1) / n_splits + ATT_TT - 1) / ATT_TT * ATT_TT;
+        split_len = ((n_keys + c->max_splits - 1) / c->max_splits + tile - 1) / tile * tile;
         n_splits = (n_keys + split_len - 1) / split_len;
     }
     a.n_splits = n_splits; a.split_len = split_len;
@@ -306,13 +310,13 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
     a.out = out_bf16 ? (void*)c->ab : (void*)c->attn;
     a.out_bf16 = out_bf16;
     a.part_o = c->part_o; a.part_ml = c->part_ml;
-    dim3 grid(n_splits * g.n_kv_heads, qblocks);
-    bool kb = is_bf16(c);
-    if (g.head_dim == 128) {
-        if (kb) hipLaunchKernelGGL((attn_split_kernel<bf16_t, 128>), grid, dim3(ATT_THREADS), 0, c->stream, a);
-        else hipLaunchKernelGGL((attn_split_kernel<float, 128>), grid, dim3(ATT_THREADS), 0, c->stream, a);
+    if (kb) {
+        dim3 grid(n_splits * g.n_kv_heads);
+        if (g.head_dim == 128) hipLaunchKernelGGL((attn_mfma_kernel<128>), grid, dim3(64 * qtiles), 0, c->stream, a);
+        else hipLaunchKernelGGL((attn_mfma_kernel<64>), grid, dim3(64 * qtiles), 0, c->stream, a);
     } else {
-        if (kb) hipLaunchKernelGGL((attn_split_kernel<bf16_t, 64>), grid, dim3(ATT_THREADS), 0, c->stream, a);
+        dim3 grid(n_splits * g.n_kv_heads, qtiles);
+        if (g.head_dim == 128) hipLaunchKernelGGL((attn_split_kernel<float, 128>), grid, dim3(ATT_THREADS), 0, c->stream, a);
         else hipLaunchKernelGGL((attn_split_kernel<float, 64>), grid, dim3(ATT_THREADS), 0, c->stream, a);
     }
     HIP_TRY(c, hipGetLastError());
@@ -605,6 +609,8 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if (g.dtype == EESD_DTYPE_BF16) {
         // the MFMA family needs 128-column steps and 32-row blocks
         if (g.d_model % 128 || g.d_ff % 128 || qd % 128 || g.vocab % 32 || g.d_model % 32 || (g.d_ff % 16)) return EESD_EINVAL;
+        // one workgroup of the MFMA attention holds all query rows of a KV head: 16 rows x group <= 128
+        if (g.n_heads / g.n_kv_heads > 8) return EESD_EINVAL;
     }
     // whenever the VALU family may see a full block of rows its activations must fit in LDS
     if ((g.dtype == EESD_DTYPE_F32 || g.gemm_path == EESD_GEMM_VALU) &&
@@ -962,7 +968,8 @@ __global__ void kv_gather_kernel(KVView kv, bool is_v, int n_tokens, float* __re
     int row = kv.n_kv_heads * kv.head_dim;
     if (idx >= n_tokens * row) return;
     int t = idx / row, r = idx - t * row, h = r / kv.head_dim, c = r - h * kv.head_dim;
-    out[idx] = load_as_f32<KT>((const KT*)kv.pool + kv_row_offset(kv, is_v, h, t) + c);
+    long long off = is_v ? kv_v_elem(kv, h, t, c) : kv_k_row(kv, h, t) + c;
+    out[idx] = load_as_f32<KT>((const KT*)kv.pool + off);
 }
 
 template <typename KT>
@@ -975,8 +982,8 @@ __global__ void kv_pattern_kernel(KVView kv, int n_tokens, unsigned salt) {
     x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
     float kval = ((float)(x & 0xffff) / 65536.0f - 0.5f) * 2.0f;
     float vval = ((float)(x >> 16) / 65536.0f - 0.5f) * 2.0f;
-    store_from_f32<KT>((KT*)kv.pool + kv_row_offset(kv, false, h, t) + c, kval);
-    store_from_f32<KT>((KT*)kv.pool + kv_row_offset(kv, true, h, t) + c, vval);
+    store_from_f32<KT>((KT*)kv.pool + kv_k_row(kv, h, t) + c, kval);
+    store_from_f32<KT>((KT*)kv.pool + kv_v_elem(kv, h, t, c), vval);
 }
 
 extern "C" int eesd_debug_fill_cache(eesd_ctx* c, int32_t n_tokens, int32_t pending_tok) {

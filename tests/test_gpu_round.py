@@ -77,6 +77,36 @@ def test_teacher_forced_rounds_match_oracle(name, temp):
     assert (s.alpha, s.beta) == (o.ts.alpha, o.ts.beta)
 
 
+@pytest.mark.parametrize("name,n_prompt", [("tiny_fp32", 333), ("gqa_bf16", 333), ("gqa_bf16", 1029)])
+def test_long_context_round_matches_oracle(name, n_prompt):
+    """Attention over a cache that spans many pages, several key splits and a ragged last tile."""
+    require_gpu()
+    shape = SHAPES[name]
+    tol = tol_of(shape)
+    o, g = make_pair(shape, 9, n_prompt + 32, 1.0, k_cap=7, kv_page=32)
+    prompt = si.make_prompt(n_prompt, shape["vocab"], 8)
+    t_ref = o.prefill(prompt)
+    g.prefill(prompt)
+    g.force_pending(t_ref)
+    for K in (7, 2):
+        ds = [o.draft_step() for _ in range(K)]
+        g.force_drafts(ds)
+        for i in range(K):
+            g.draft_step(sync=False)
+        p_logits = o.verify()
+        g.verify()
+        for i in range(K):
+            assert rel_err(g.draft_logits(i), o.q_logits[i]) < tol, ("draft logits", K, i)
+        for i in range(K + 1):
+            assert rel_err(g.verify_logits(i), p_logits[i]) < tol, ("verify logits", K, i)
+        a, y = o.accept()
+        g.accept()
+        o.rollback(a, y)
+        g.rollback(a)
+        g.force_pending(y)
+    _check_caches(o, g, o.kv_len, tol)
+
+
 @pytest.mark.parametrize("name", list(SHAPES))
 def test_verify_block_equals_sequential_steps_on_gpu(name):
     require_gpu()
