@@ -210,7 +210,7 @@ int eesd_debug_profile_begin(eesd_ctx* ctx, int32_t family, int32_t epilogue_kin
 int eesd_debug_profile_end(eesd_ctx* ctx, int32_t* n_launches, double* total_ms);
 
 /* Launch-shape knobs for benchmark sweeps (process-wide; 0 restores the built-in heuristic):
- * "valu_nw", "valu_tpw", "valu_rp", "mfma_t", "mfma_nw", "attn_split", "mfma_min_m". */
+ * "valu_nw", "valu_tpw", "valu_rp", "mfma_nw", "mfma_ksplit", "mfma_tile", "attn_split", "mfma_min_m". */
 int eesd_set_tunable(const char* name, int value);
 
 /* ---- stand-alone kernels (device buffers in, host results out) ----------------------- */
@@ -223,9 +223,10 @@ int eesd_op_accept(const float* p_rows, const float* q_rows, const int32_t* draf
  * inverse-CDF draw with u (temperature 0: argmax, probs untouched).  *token: HOST. */
 int eesd_op_softmax_sample(const float* logits, float* probs, int32_t vocab, float temperature, double u,
                            void* hip_stream, int32_t* token);
-/* Y[m][r] = sum_k X[m][k] W[r][k] for M <= 16 rows: the weight-streaming product of the draft
- * (M = 1) and verify (M = K+1) passes without prologue or epilogue.  W: DEVICE [out][in] in
- * dtype; X: DEVICE fp32 [M][in]; Y: DEVICE fp32 [M][out]; path: EESD_GEMM_*. */
+/* Y[m][r] = sum_k X[m][k] W[r][k]: the weight-streaming product of the draft (M = 1), verify
+ * (M = K+1 <= 16) and prefill (M <= 128, bf16 MFMA family, out % 64 == 0, in % 256 == 0) passes
+ * without prologue or epilogue.  W: DEVICE [out][in] in dtype; X: DEVICE fp32 [M][in];
+ * Y: DEVICE fp32 [M][out]; path: EESD_GEMM_*. */
 int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,
                  int32_t dtype, int32_t path, void* hip_stream);
 

@@ -19,7 +19,8 @@
 #include "gemm.hiph"
 #include "sampling.hiph"
 
-#define MAX_ROWS 16  // rows per pass: 1 (draft) .. k_cap + 1 (verify), prefill chunk
+#define MAX_ROWS 16    // rows of a decoding pass: 1 (draft) .. k_cap + 1 (verify)
+#define PREFILL_ROWS 128  // rows of a prefill block when the tiled MFMA product applies
 
 // ---------------------------------------------------------------------------------------------
 // tunables (benchmark sweeps)
@@ -27,16 +28,17 @@
 static int g_valu_nw = 0;      // waves per workgroup of the VALU product (0 = heuristic)
 static int g_valu_tpw = 0;     // tasks per wave
 static int g_valu_rp = 0;      // row pairs per task (1 or 2)
-static int g_mfma_t = 0;       // 16-row tiles per block half (1 or 2)
+static int g_mfma_ksplit = 0;  // cross-workgroup K split of the residual products (0 = heuristic)
 static int g_mfma_nw = 0;      // waves per workgroup of the MFMA product
 static int g_attn_split = 0;   // keys per attention split
-static int g_mfma_min_m = 2;   // AUTO: smallest M that takes the MFMA family on bf16 weights
+static int g_mfma_tile = 0;    // 1: blocks of <= 16 rows also take the LDS-shared tile kernel
+static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
 
 extern "C" int eesd_set_tunable(const char* name, int value) {
     if (!name) return EESD_EINVAL;
     struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
-                                             {"mfma_t", &g_mfma_t}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
-                                             {"mfma_min_m", &g_mfma_min_m}};
+                                             {"mfma_ksplit", &g_mfma_ksplit}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
+                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}};
     for (auto& e : t)
         if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
     return EESD_EINVAL;
@@ -100,11 +102,12 @@ struct eesd_ctx {
     int mapped_pages;
 
     // scratch (device)
-    float *x, *q, *attn, *act, *logits, *p_rows, *q_logits, *q_rows, *part_o, *part_ml, *rope_cs;
+    float *x, *q, *attn, *act, *logits, *p_rows, *q_logits, *q_rows, *part_o, *part_ml, *rope_cs, *part;
     bf16_t *xb, *ab, *actb;
     int32_t *blk_tok, *prompt_dev, *result_dev;
     int32_t *h_result, *h_prompt;  // pinned
     int max_splits;
+    int row_cap;           // rows the activation buffers hold (16, or PREFILL_ROWS)
     hipEvent_t ev[4];
 
     // per-kernel timing of one class of product launches (benchmark hook)
@@ -205,40 +208,57 @@ static hipError_t launch_valu(const GemmP& p, bool bf16, hipStream_t st) {
     return bf16 ? launch_valu_m<bf16_t, EPI>(p, st) : launch_valu_m<float, EPI>(p, st);
 }
 
-template <int EPI, int T>
-static hipError_t launch_mfma_t(const GemmP& p, int n_blocks, int nw, hipStream_t st) {
-    size_t lds = (size_t)nw * 2 * T * 64 * 16;  // split-K reduction
-    auto fn = gemm_mfma_kernel<EPI, T>;
+// cross-workgroup K split of a residual product (its partial sums are folded by resid_norm_kernel)
+#define MFMA_MAX_KSPLIT 8
+static int mfma_ksplit(int out_rows, int in_dim) {
+    if (g_mfma_ksplit) return std::min(g_mfma_ksplit, MFMA_MAX_KSPLIT);
+    const int n_tiles = out_rows / 16, steps = in_dim / 128;
+    int ks = 1;
+    while (ks < MFMA_MAX_KSPLIT && n_tiles * ks < 1024 && steps / (ks * 2) >= 4) ks *= 2;
+    return ks;
+}
+
+static bool tile_shape_ok(int out_rows, int in_dim) { return (out_rows / 16) % 4 == 0 && in_dim % GT_KC == 0; }
+
+template <int EPI, int NB>
+static hipError_t launch_tile_t(const GemmP& p, int ksplit, hipStream_t st) {
+    size_t lds = (size_t)NB * 16 * GT_RS * sizeof(bf16_t);
+    auto fn = gemm_tile_kernel<EPI, NB>;
     hipError_t e = allow_lds((const void*)fn, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, dim3(n_blocks), dim3(nw * 64), lds, st, p);
+    hipLaunchKernelGGL(fn, dim3(p.out_rows / 64, ksplit), dim3(256), lds, st, p);
     return hipGetLastError();
 }
 
 template <int EPI>
-static hipError_t launch_mfma(const GemmP& p, hipStream_t st) {
-    int unit = (EPI == EPI_QKV) ? p.head_dim / 2 : p.out_rows / 2;
-    // T tiles of 16 rows per block half: 16*T must divide `unit`
-    int T = g_mfma_t ? g_mfma_t : 1;
-    if (unit % (16 * T)) T = 1;
-    int n_blocks = p.out_rows / (32 * T);
-    int steps = p.in_dim / 128;
+static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
+    if ((p.M > 16 || g_mfma_tile) && tile_shape_ok(p.out_rows, p.in_dim)) {
+        if (p.M <= 16) return launch_tile_t<EPI, 1>(p, ksplit, st);
+        if (p.M <= 32) return launch_tile_t<EPI, 2>(p, ksplit, st);
+        if (p.M <= 64) return launch_tile_t<EPI, 4>(p, ksplit, st);
+        if (p.M <= 128) return launch_tile_t<EPI, 8>(p, ksplit, st);
+        return hipErrorInvalidValue;
+    }
+    if (p.M > 16) return hipErrorInvalidValue;
+    const int n_tiles = p.out_rows / 16, steps = p.in_dim / 128;
     int nw = g_mfma_nw;
     if (!nw) {
-        // about 1-2 thousand waves over the chip, at least two 128-column steps per wave
-        nw = 1;
-        while (nw < 8 && n_blocks * nw < 1024 && steps / (nw * 2) >= 2) nw *= 2;
+        // 2-4 thousand waves over the chip, at least two 128-column steps per wave
+        nw = 2;
+        while (nw < 4 && n_tiles * ksplit * nw < 2560 && steps / (ksplit * nw * 2) >= 2) nw *= 2;
+        if (steps / ksplit < 2) nw = 1;
     }
-    nw = std::max(nw, T);
-    nw = std::min(nw, std::max(steps, T));
-    return T == 2 ? launch_mfma_t<EPI, 2>(p, n_blocks, nw, st) : launch_mfma_t<EPI, 1>(p, n_blocks, nw, st);
+    nw = std::max(1, std::min(nw, 16));
+    size_t lds = (size_t)nw * 64 * 16;
+    hipLaunchKernelGGL((gemm_mfma_kernel<EPI>), dim3(n_tiles, ksplit), dim3(nw * 64), lds, st, p);
+    return hipGetLastError();
 }
 
 static bool mfma_shape_ok(int out, int in, int epi, int head_dim) {
     if (in % 128) return false;
-    if (epi == EPI_QKV) return head_dim % 32 == 0 && out % head_dim == 0;
-    if (epi == EPI_SWIGLU) return (out / 2) % 16 == 0;
-    return out % 32 == 0;
+    if (epi == EPI_QKV) return head_dim % 16 == 0 && out % head_dim == 0;
+    if (epi == EPI_SWIGLU) return (out / 2) % 8 == 0;
+    return out % 16 == 0;
 }
 
 // true -> MFMA family
@@ -252,7 +272,7 @@ static bool pick_mfma(const eesd_ctx* c, int M) {
 #define PROF_MAX_PAIRS 8192
 
 template <int EPI>
-static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p) {
+static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
     bool prof = c->prof_family == (mfma ? 1 : 0) && c->prof_epi == EPI && (c->prof_in == 0 || c->prof_in == p.in_dim) &&
                 c->prof_used < PROF_MAX_PAIRS;
     if (prof) {
@@ -263,7 +283,7 @@ static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p) {
         }
         HIP_TRY(c, hipEventRecord(c->prof_ev[2 * c->prof_used], c->stream));
     }
-    HIP_TRY(c, mfma ? launch_mfma<EPI>(p, c->stream) : launch_valu<EPI>(p, is_bf16(c), c->stream));
+    HIP_TRY(c, mfma ? launch_mfma<EPI>(p, ksplit, c->stream) : launch_valu<EPI>(p, is_bf16(c), c->stream));
     if (prof) {
         HIP_TRY(c, hipEventRecord(c->prof_ev[2 * c->prof_used + 1], c->stream));
         ++c->prof_used;
@@ -301,8 +321,9 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
     }
     split_len = (split_len + tile - 1) / tile * tile;
     int n_splits = (n_keys + split_len - 1) / split_len;
-    if (n_splits > c->max_splits) {
-        split_len = ((n_keys + c->max_splits - 1) / c->max_splits + tile - 1) / tile * tile;
+    const int max_splits = std::max(1, std::min(c->max_splits, (MAX_ROWS * c->max_splits) / M));   // partial buffers hold 16 rows x max_splits
+    if (n_splits > max_splits) {
+        split_len = ((n_keys + max_splits - 1) / max_splits + tile - 1) / tile * tile;
         n_splits = (n_keys + split_len - 1) / split_len;
     }
     a.n_splits = n_splits; a.split_len = split_len;
@@ -311,9 +332,10 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
     a.out_bf16 = out_bf16;
     a.part_o = c->part_o; a.part_ml = c->part_ml;
     if (kb) {
-        dim3 grid(n_splits * g.n_kv_heads);
-        if (g.head_dim == 128) hipLaunchKernelGGL((attn_mfma_kernel<128>), grid, dim3(64 * qtiles), 0, c->stream, a);
-        else hipLaunchKernelGGL((attn_mfma_kernel<64>), grid, dim3(64 * qtiles), 0, c->stream, a);
+        dim3 grid(n_splits * g.n_kv_heads, (qtiles + 7) / 8);
+        const int nwq = std::min(qtiles, 8);
+        if (g.head_dim == 128) hipLaunchKernelGGL((attn_mfma_kernel<128>), grid, dim3(64 * nwq), 0, c->stream, a);
+        else hipLaunchKernelGGL((attn_mfma_kernel<64>), grid, dim3(64 * nwq), 0, c->stream, a);
     } else {
         dim3 grid(n_splits * g.n_kv_heads, qtiles);
         if (g.head_dim == 128) hipLaunchKernelGGL((attn_split_kernel<float, 128>), grid, dim3(ATT_THREADS), 0, c->stream, a);
@@ -344,31 +366,40 @@ static void fill_qkv(eesd_ctx* c, GemmP& p, int cache, int pos0, int head0) {
     p.kv_bf16 = is_bf16(c);
 }
 
+static int launch_resid_norm(eesd_ctx* c, int M, int ksplit, const void* gain) {
+    const int d = c->cfg.d_model;
+    hipLaunchKernelGGL((resid_norm_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->stream, c->x, d, c->part, ksplit, c->row_cap, d, (const bf16_t*)gain,
+                       c->cfg.rms_eps, d, c->xb, d);
+    HIP_TRY(c, hipGetLastError());
+    return EESD_OK;
+}
+
 // One decoder layer on the M rows in c->x at positions pos0.. ; K/V go to `cache`.
-static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M, int pos0, bool mfma) {
+// MFMA family: on entry c->xb holds RMSNorm(x; lw.attn_norm) in bf16; on exit it holds
+// RMSNorm(x; next_gain) for whatever consumes the layer's output next.
+static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M, int pos0, bool mfma, const void* next_gain) {
     const eesd_config& g = c->cfg;
     const int d = g.d_model, hd = g.head_dim, qd = g.n_heads * hd, f = g.d_ff;
     const int qkv_rows = (g.n_heads + 2 * g.n_kv_heads) * hd;
     int rc;
     if (mfma) {
-        rc = launch_rmsnorm_bf16(c, c->x, M, lw.attn_norm, c->xb, d);
-        if (rc) return rc;
         GemmP p = gemm_base(lw.wqkv, c->xb, d, M, qkv_rows, d);
         fill_qkv(c, p, cache, pos0, 0);
         if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
-        rc = launch_attention(c, cache, M, pos0, true);
-        if (rc) return rc;
+        if ((rc = launch_attention(c, cache, M, pos0, true))) return rc;
+        int ks = mfma_ksplit(d, qd);
         p = gemm_base(lw.wo, c->ab, qd, M, d, qd);
-        p.Y = c->x; p.ldy = d;
-        if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
-        rc = launch_rmsnorm_bf16(c, c->x, M, lw.ffn_norm, c->xb, d);
-        if (rc) return rc;
+        p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->row_cap;
+        if ((rc = gemm_launch<EPI_RESID>(c, true, p, ks))) return rc;
+        if ((rc = launch_resid_norm(c, M, ks, lw.ffn_norm))) return rc;
         p = gemm_base(lw.w_gate_up, c->xb, d, M, 2 * f, d);
         p.Y = c->actb; p.ldy = f; p.y_bf16 = 1;
         if ((rc = gemm_launch<EPI_SWIGLU>(c, true, p))) return rc;
+        ks = mfma_ksplit(d, f);
         p = gemm_base(lw.w_down, c->actb, f, M, d, f);
-        p.Y = c->x; p.ldy = d;
-        if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
+        p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->row_cap;
+        if ((rc = gemm_launch<EPI_RESID>(c, true, p, ks))) return rc;
+        if ((rc = launch_resid_norm(c, M, ks, next_gain))) return rc;
     } else {
         GemmP p = gemm_base(lw.wqkv, c->x, d, M, qkv_rows, d);
         p.gain = lw.attn_norm; p.eps = g.rms_eps;
@@ -392,6 +423,7 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
 
 // Keys and values of the early-exit layer for the M rows in c->x (layer-N hidden states):
 // only the k and v rows of its fused QKV matrix are streamed.
+// MFMA family: c->xb holds RMSNorm(x; ee_layer.attn_norm) on entry.
 static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
     const eesd_config& g = c->cfg;
     const int d = g.d_model, hd = g.head_dim;
@@ -400,8 +432,6 @@ static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
     const int rows = 2 * g.n_kv_heads * hd;
     int rc;
     if (mfma) {
-        rc = launch_rmsnorm_bf16(c, c->x, M, c->w.ee_layer.attn_norm, c->xb, d);
-        if (rc) return rc;
         GemmP p = gemm_base(wkv, c->xb, d, M, rows, d);
         fill_qkv(c, p, g.n_layers, pos0, g.n_heads);
         if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
@@ -414,20 +444,18 @@ static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
     return EESD_OK;
 }
 
-// logits[m][:] = RMSNorm(x[m]; norm) head^T for rows x0 .. x0+M-1 of c->x
+// logits[m][:] = RMSNorm(x[m]; norm) head^T for rows x0 .. x0+M-1 of c->x.
+// MFMA family: the normalised rows are already in c->xb.
 static int run_head(eesd_ctx* c, const void* norm, const void* head, int x0, int M, float* logits, bool mfma) {
     const eesd_config& g = c->cfg;
     const int d = g.d_model;
-    const float* xr = c->x + (size_t)x0 * d;
     int rc;
     if (mfma) {
-        rc = launch_rmsnorm_bf16(c, xr, M, norm, c->xb, d);
-        if (rc) return rc;
-        GemmP p = gemm_base(head, c->xb, d, M, g.vocab, d);
+        GemmP p = gemm_base(head, c->xb + (size_t)x0 * d, d, M, g.vocab, d);
         p.Y = logits; p.ldy = g.vocab;
         if ((rc = gemm_launch<EPI_PLAIN>(c, true, p))) return rc;
     } else {
-        GemmP p = gemm_base(head, xr, d, M, g.vocab, d);
+        GemmP p = gemm_base(head, c->x + (size_t)x0 * d, d, M, g.vocab, d);
         p.gain = norm; p.eps = g.rms_eps;
         p.Y = logits; p.ldy = g.vocab;
         if ((rc = gemm_launch<EPI_PLAIN>(c, false, p))) return rc;
@@ -445,17 +473,21 @@ static int launch_embed(eesd_ctx* c, const int32_t* tok_dev, int M) {
 }
 
 // Target forward over M rows whose tokens are tok_dev[0..M) at positions pos0.. :
-// all L layers (plus the early-exit layer's K/V after layer N); leaves hidden states in c->x.
-static int run_target_rows(eesd_ctx* c, const int32_t* tok_dev, int M, int pos0) {
-    const bool mfma = pick_mfma(c, M);
+// all L layers (plus the early-exit layer's K/V after layer N); leaves hidden states in c->x
+// and, in the MFMA family, RMSNorm(x; final_norm) in c->xb.
+static int run_target_rows(eesd_ctx* c, const int32_t* tok_dev, int M, int pos0, bool mfma) {
+    const eesd_config& g = c->cfg;
     int rc = launch_embed(c, tok_dev, M);
     if (rc) return rc;
-    for (int l = 0; l < c->cfg.n_layers; ++l) {
-        rc = run_layer(c, c->layers[l], l, M, pos0, mfma);
-        if (rc) return rc;
-        if (l + 1 == c->cfg.n_draft_layers) {
-            rc = run_ee_kv_fill(c, M, pos0, mfma);
-            if (rc) return rc;
+    if (mfma && (rc = launch_rmsnorm_bf16(c, c->x, M, c->layers[0].attn_norm, c->xb, g.d_model))) return rc;
+    for (int l = 0; l < g.n_layers; ++l) {
+        const bool ee_next = (l + 1 == g.n_draft_layers);
+        const void* next_gain = ee_next ? c->w.ee_layer.attn_norm : (l + 1 < g.n_layers ? c->layers[l + 1].attn_norm : c->w.final_norm);
+        if ((rc = run_layer(c, c->layers[l], l, M, pos0, mfma, next_gain))) return rc;
+        if (ee_next) {
+            if ((rc = run_ee_kv_fill(c, M, pos0, mfma))) return rc;
+            // N < L always: the next target layer wants its own normalised copy
+            if (mfma && (rc = launch_rmsnorm_bf16(c, c->x, M, c->layers[l + 1].attn_norm, c->xb, g.d_model))) return rc;
         }
     }
     return EESD_OK;
@@ -580,7 +612,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
-                   c->part_ml, c->rope_cs, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev};
+                   c->part_ml, c->rope_cs, c->part, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev};
     for (void* p : dev)
         if (p) hipFree(p);
     if (c->h_table) hipHostFree(c->h_table);
@@ -611,6 +643,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
         if (g.d_model % 128 || g.d_ff % 128 || qd % 128 || g.vocab % 32 || g.d_model % 32 || (g.d_ff % 16)) return EESD_EINVAL;
         // one workgroup of the MFMA attention holds all query rows of a KV head: 16 rows x group <= 128
         if (g.n_heads / g.n_kv_heads > 8) return EESD_EINVAL;
+        if (g.d_model > RN_MAX_PIECES * 8 * 1024) return EESD_EINVAL;
     }
     // whenever the VALU family may see a full block of rows its activations must fit in LDS
     if ((g.dtype == EESD_DTYPE_F32 || g.gemm_path == EESD_GEMM_VALU) &&
@@ -635,7 +668,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->stream = (hipStream_t)hip_stream;
     c->state = ST_CREATED;
     c->kv_pool = nullptr; c->d_table = nullptr; c->h_table = nullptr;
-    c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = nullptr;
+    c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = c->part = nullptr;
     c->xb = c->ab = c->actb = nullptr;
     c->blk_tok = c->prompt_dev = c->result_dev = nullptr;
     c->h_result = c->h_prompt = nullptr;
@@ -669,26 +702,34 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
 
     const int d = g.d_model, f = g.d_ff, V = g.vocab;
     c->max_splits = 64;
-    if ((rc = dev_alloc(c, &c->x, (size_t)MAX_ROWS * d))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->q, (size_t)MAX_ROWS * qd))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->attn, (size_t)MAX_ROWS * qd))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->act, (size_t)MAX_ROWS * f))) return bail(rc);
+    {
+        const int qkv_rows = (g.n_heads + 2 * g.n_kv_heads) * g.head_dim, kv_rows = 2 * g.n_kv_heads * g.head_dim;
+        bool tiled = g.dtype == EESD_DTYPE_BF16 && g.gemm_path != EESD_GEMM_VALU && tile_shape_ok(qkv_rows, d) && tile_shape_ok(kv_rows, d) &&
+                     tile_shape_ok(d, qd) && tile_shape_ok(2 * f, d) && tile_shape_ok(d, f) && tile_shape_ok(V, d);
+        c->row_cap = tiled ? PREFILL_ROWS : MAX_ROWS;
+    }
+    const size_t R = c->row_cap;
+    if ((rc = dev_alloc(c, &c->x, R * d))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->q, R * qd))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->attn, R * qd))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->act, R * f))) return bail(rc);
     if ((rc = dev_alloc(c, &c->logits, (size_t)MAX_ROWS * V))) return bail(rc);
     if ((rc = dev_alloc(c, &c->p_rows, (size_t)MAX_ROWS * V))) return bail(rc);
     if ((rc = dev_alloc(c, &c->q_logits, (size_t)g.k_cap * V))) return bail(rc);
     if ((rc = dev_alloc(c, &c->q_rows, (size_t)g.k_cap * V))) return bail(rc);
     if ((rc = dev_alloc(c, &c->part_o, (size_t)MAX_ROWS * g.n_heads * c->max_splits * g.head_dim))) return bail(rc);
     if ((rc = dev_alloc(c, &c->part_ml, (size_t)MAX_ROWS * g.n_heads * c->max_splits * 2))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->xb, (size_t)MAX_ROWS * d))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->ab, (size_t)MAX_ROWS * qd))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->actb, (size_t)MAX_ROWS * f))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->part, (size_t)MFMA_MAX_KSPLIT * R * d))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->xb, R * d))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->ab, R * qd))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->actb, R * f))) return bail(rc);
     if ((rc = dev_alloc(c, &c->blk_tok, (size_t)MAX_ROWS + 1))) return bail(rc);
     if ((rc = dev_alloc(c, &c->prompt_dev, (size_t)g.max_seq))) return bail(rc);
     if ((rc = dev_alloc(c, &c->result_dev, (size_t)4))) return bail(rc);
     // rows of the bf16 activation buffers past M are read (and ignored) by the MFMA product
-    hipMemset(c->xb, 0, sizeof(bf16_t) * MAX_ROWS * d);
-    hipMemset(c->ab, 0, sizeof(bf16_t) * MAX_ROWS * qd);
-    hipMemset(c->actb, 0, sizeof(bf16_t) * MAX_ROWS * f);
+    hipMemset(c->xb, 0, sizeof(bf16_t) * R * d);
+    hipMemset(c->ab, 0, sizeof(bf16_t) * R * qd);
+    hipMemset(c->actb, 0, sizeof(bf16_t) * R * f);
     hipMemset(c->d_table, 0, sizeof(int32_t) * c->n_pages);
     hipMemset(c->kv_pool, 0, pool_bytes);
 
@@ -750,14 +791,16 @@ extern "C" int eesd_prefill(eesd_ctx* c, const int32_t* prompt, int32_t n, int32
     int rc = ensure_pages(c, n);
     if (rc) return rc;
     int last_m = 0;
-    for (int p0 = 0; p0 < n; p0 += MAX_ROWS) {
-        int m = std::min(MAX_ROWS, n - p0);
-        rc = run_target_rows(c, c->prompt_dev + p0, m, p0);
+    bool last_mfma = false;
+    for (int p0 = 0; p0 < n; p0 += c->row_cap) {
+        int m = std::min(c->row_cap, n - p0);
+        last_mfma = pick_mfma(c, m);
+        rc = run_target_rows(c, c->prompt_dev + p0, m, p0, last_mfma);
         if (rc) return rc;
         last_m = m;
     }
-    // logits of the last prompt position only
-    rc = run_head(c, c->w.final_norm, c->w.lm_head, last_m - 1, 1, c->logits, pick_mfma(c, 1));
+    // logits of the last prompt position only (the family of the last block left its input ready)
+    rc = run_head(c, c->w.final_norm, c->w.lm_head, last_m - 1, 1, c->logits, last_mfma);
     if (rc) return rc;
     double u = uniform53(g.seed, STREAM_RESAMPLE, 0, 0, 0);
     hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, c->logits, c->p_rows, g.vocab, inv_temperature(c),
@@ -786,9 +829,12 @@ extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
     const bool mfma = pick_mfma(c, 1);
     rc = launch_embed(c, c->blk_tok + i, 1);
     if (rc) return rc;
-    for (int l = 0; l < g.n_draft_layers; ++l)
-        if ((rc = run_layer(c, c->layers[l], l, 1, pos, mfma))) return rc;
-    if ((rc = run_layer(c, c->w.ee_layer, g.n_layers, 1, pos, mfma))) return rc;
+    if (mfma && (rc = launch_rmsnorm_bf16(c, c->x, 1, c->layers[0].attn_norm, c->xb, g.d_model))) return rc;
+    for (int l = 0; l < g.n_draft_layers; ++l) {
+        const void* next_gain = l + 1 < g.n_draft_layers ? c->layers[l + 1].attn_norm : c->w.ee_layer.attn_norm;
+        if ((rc = run_layer(c, c->layers[l], l, 1, pos, mfma, next_gain))) return rc;
+    }
+    if ((rc = run_layer(c, c->w.ee_layer, g.n_layers, 1, pos, mfma, c->w.ee_norm))) return rc;
     float* ql = c->q_logits + (size_t)i * g.vocab;
     if ((rc = run_head(c, c->w.ee_norm, c->w.ee_head, 0, 1, ql, mfma))) return rc;
     int forced = -1;
@@ -814,8 +860,9 @@ extern "C" int eesd_verify(eesd_ctx* c) {
     if (c->kv_len + M > g.max_seq) return fail(c, EESD_ERANGE, "verify: %d rows at %d exceed max_seq %d", M, c->kv_len, g.max_seq);
     int rc = ensure_pages(c, c->kv_len + M);
     if (rc) return rc;
-    if ((rc = run_target_rows(c, c->blk_tok, M, c->kv_len))) return rc;
-    if ((rc = run_head(c, c->w.final_norm, c->w.lm_head, 0, M, c->logits, pick_mfma(c, M)))) return rc;
+    const bool mfma = pick_mfma(c, M);
+    if ((rc = run_target_rows(c, c->blk_tok, M, c->kv_len, mfma))) return rc;
+    if ((rc = run_head(c, c->w.final_norm, c->w.lm_head, 0, M, c->logits, mfma))) return rc;
     c->state = ST_VERIFIED;
     return EESD_OK;
 }
@@ -1134,7 +1181,7 @@ extern "C" int eesd_op_softmax_sample(const float* logits, float* probs, int32_t
 
 extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in, int32_t dtype, int32_t path,
                             void* hip_stream) {
-    if (!W || !X || !Y || M < 1 || M > MAX_ROWS || out < 2 || in < 8) return EESD_EINVAL;
+    if (!W || !X || !Y || M < 1 || M > PREFILL_ROWS || out < 2 || in < 8) return EESD_EINVAL;
     if (dtype != EESD_DTYPE_F32 && dtype != EESD_DTYPE_BF16) return EESD_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     const bool b16 = dtype == EESD_DTYPE_BF16;
@@ -1142,10 +1189,11 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
     if (path == EESD_GEMM_MFMA && !b16) return EESD_EINVAL;
     if (mfma) {
         if (!mfma_shape_ok(out, in, EPI_PLAIN, 0)) return EESD_EINVAL;
+        if (M > MAX_ROWS && !tile_shape_ok(out, in)) return EESD_EINVAL;
         // bf16 staging rows of the activations: one buffer per process, grown on demand, kept
         static bf16_t* xb = nullptr;
         static size_t xb_elems = 0;
-        const size_t need = (size_t)MAX_ROWS * in;
+        const size_t need = (size_t)PREFILL_ROWS * in;
         if (need > xb_elems) {
             if (hipDeviceSynchronize() != hipSuccess) return EESD_EDEVICE;
             if (xb) hipFree(xb);
@@ -1159,11 +1207,11 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
         if (e == hipSuccess) {
             GemmP p = gemm_base(W, xb, in, M, out, in);
             p.Y = Y; p.ldy = out;
-            e = launch_mfma<EPI_PLAIN>(p, st);
+            e = launch_mfma<EPI_PLAIN>(p, 1, st);
         }
         return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
     }
-    if (in % (b16 ? 8 : 4) || out % 2 || valu_lds_bytes(M, in) > 150 * 1024) return EESD_EINVAL;
+    if (M > MAX_ROWS || in % (b16 ? 8 : 4) || out % 2 || valu_lds_bytes(M, in) > 150 * 1024) return EESD_EINVAL;
     GemmP p = gemm_base(W, X, in, M, out, in);
     p.Y = Y; p.ldy = out;
     hipError_t e = launch_valu<EPI_PLAIN>(p, b16, st);

@@ -45,23 +45,34 @@ def test_gemm_valu_bf16(M, out, inn):
 
 
 @pytest.mark.parametrize("M", [1, 2, 5, 11, 16])
-@pytest.mark.parametrize("out,inn", [(1024, 512), (5120, 5120), (160, 13824), (32000, 1024), (96, 128)])
+@pytest.mark.parametrize("out,inn", [(1024, 512), (5120, 5120), (160, 13824), (32000, 1024), (80, 128)])
 def test_gemm_mfma_bf16(M, out, inn):
     require_gpu()
     assert _gemm_case(M, out, inn, torch.bfloat16, _pk().GEMM_MFMA, 3) < TOL_BF16
 
 
-@pytest.mark.parametrize("t,nw", [(1, 1), (1, 4), (1, 16), (2, 2), (2, 8)])
-def test_gemm_mfma_launch_shapes(t, nw):
+@pytest.mark.parametrize("M", [1, 7, 16, 17, 40, 64, 100, 128])
+@pytest.mark.parametrize("out,inn", [(1024, 512), (5120, 5120), (320, 13824), (32000, 1024), (64, 256)])
+def test_gemm_tile_kernel_bf16(M, out, inn):
+    """The LDS-shared tile kernel: prefill blocks (M > 16) and, forced, verify-sized blocks."""
     require_gpu()
     pk = _pk()
     try:
-        pk.set_tunable("mfma_t", t)
+        pk.set_tunable("mfma_tile", 1)
+        assert _gemm_case(M, out, inn, torch.bfloat16, pk.GEMM_MFMA, 6) < TOL_BF16
+    finally:
+        pk.set_tunable("mfma_tile", 0)
+
+
+@pytest.mark.parametrize("nw", [1, 2, 4, 16])
+def test_gemm_mfma_launch_shapes(nw):
+    require_gpu()
+    pk = _pk()
+    try:
         pk.set_tunable("mfma_nw", nw)
         assert _gemm_case(7, 2048, 2048, torch.bfloat16, pk.GEMM_MFMA, 4) < TOL_BF16
-        assert _gemm_case(16, 192, 1280, torch.bfloat16, pk.GEMM_MFMA, 5) < TOL_BF16
+        assert _gemm_case(16, 176, 1280, torch.bfloat16, pk.GEMM_MFMA, 5) < TOL_BF16
     finally:
-        pk.set_tunable("mfma_t", 0)
         pk.set_tunable("mfma_nw", 0)
 
 

@@ -77,6 +77,46 @@ def test_teacher_forced_rounds_match_oracle(name, temp):
     assert (s.alpha, s.beta) == (o.ts.alpha, o.ts.beta)
 
 
+@pytest.mark.parametrize("path,ksplit", [("valu", 0), ("mfma", 1), ("mfma", 2), ("mfma", 8), ("auto", 4), ("tile", 0), ("tile", 2)])
+def test_kernel_families_and_k_splits_match_oracle(path, ksplit):
+    """The bf16 model with one kernel family forced for every pass (single-row MFMA, multi-row
+    VALU) and with the residual products split over 1..8 workgroups along K."""
+    require_gpu()
+    import paper_2406_03853_amd as pk
+    shape = SHAPES["gqa_bf16"]
+    tol = tol_of(shape)
+    gp = {"valu": pk.GEMM_VALU, "mfma": pk.GEMM_MFMA, "auto": pk.GEMM_AUTO, "tile": pk.GEMM_AUTO}[path]
+    try:
+        pk.set_tunable("mfma_ksplit", ksplit)
+        pk.set_tunable("mfma_tile", 1 if path == "tile" else 0)
+        o, g = make_pair(shape, 11, 96, 1.0, k_cap=4, gemm_path=gp)
+        prompt = si.make_prompt(21, shape["vocab"], 5)
+        t_ref = o.prefill(prompt)
+        g.prefill(prompt)
+        assert rel_err(g.verify_logits(0), o.prefill_logits) < tol
+        g.force_pending(t_ref)
+        for K in (4, 1):
+            ds = [o.draft_step() for _ in range(K)]
+            g.force_drafts(ds)
+            for i in range(K):
+                g.draft_step(sync=False)
+            p_logits = o.verify()
+            g.verify()
+            for i in range(K):
+                assert rel_err(g.draft_logits(i), o.q_logits[i]) < tol
+            for i in range(K + 1):
+                assert rel_err(g.verify_logits(i), p_logits[i]) < tol
+            a, y = o.accept()
+            g.accept()
+            o.rollback(a, y)
+            g.rollback(a)
+            g.force_pending(y)
+        _check_caches(o, g, o.kv_len, tol)
+    finally:
+        pk.set_tunable("mfma_ksplit", 0)
+        pk.set_tunable("mfma_tile", 0)
+
+
 @pytest.mark.parametrize("name,n_prompt", [("tiny_fp32", 333), ("gqa_bf16", 333), ("gqa_bf16", 1029)])
 def test_long_context_round_matches_oracle(name, n_prompt):
     """Attention over a cache that spans many pages, several key splits and a ragged last tile."""
