@@ -80,6 +80,16 @@ def cpu_baseline(w_gpu, shape, temperature, mean_k, mean_commit, si):
                 draft_step_s=t_draft_full, verify_s=t_verify_full)
 
 
+def stored_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed hardware-counter summary
+    (profiles/hbm_traffic.json, written from two rocprofv3 --pmc runs), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        return json.load(f).get(workload, {}).get("bytes_per_launch")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -88,6 +98,8 @@ def main():
     ap.add_argument("--workload", default="70b", choices=sorted(WORKLOADS))
     ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run the library's 1 GiB copy kernel a few times (reference for hardware-counter runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (batch-1 decoding does not shard across GPUs here); "
@@ -113,6 +125,13 @@ def main():
     ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64)
     prompt = si.make_prompt(n_prompt, shape["vocab"], 0)
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            pk.calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         ctx.generate(prompt, max_new)
     torch.cuda.synchronize()
@@ -155,11 +174,11 @@ def main():
         "config": {"workload": f"full EESD generation, {shape['name']} (L={L}, N={N}), random weights seed {wseed}, "
                                f"prompt {n_prompt} uniform ids, {max_new} new tokens, Beta-TS K cap {k_cap}, "
                                f"temperature {args.temperature:g}, batch 1",
-                   "prefill": "included in every step (16-row blocks through the verify path)"},
+                   "prefill": "included in every step (128-row blocks, tiled MFMA product)"},
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<SWIGLU> (gate/up product of verify and prefill blocks)" if bf16
                      else "gemm_valu_kernel<SWIGLU>",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "launches_timed": n_launch, "avg_kernel_us": avg_kernel_s * 1e6,
+                     "traffic": stored_traffic(args.workload), "launches_timed": n_launch, "avg_kernel_us": avg_kernel_s * 1e6,
                      "bytes_per_launch": kernel_bytes},
         "passes": {"draft_step_ms": ms_draft, "verify_ms": ms_verify, "accept_ms": ms_accept,
                    "draft_step_GBps": b_draft / (ms_draft * 1e-3) / 1e9 if ms_draft else None,

@@ -209,6 +209,11 @@ int eesd_debug_fill_cache(eesd_ctx* ctx, int32_t n_tokens, int32_t pending_tok);
 int eesd_debug_profile_begin(eesd_ctx* ctx, int32_t family, int32_t epilogue_kind, int32_t in_dim);
 int eesd_debug_profile_end(eesd_ctx* ctx, int32_t* n_launches, double* total_ms);
 
+/* Copies `bytes` (a multiple of 16) DEVICE to DEVICE with a plain streaming kernel named
+ * eesd_calibration_copy_kernel: hardware-counter runs are scaled by what the same counters read
+ * for this kernel, whose traffic is known (bytes read + bytes written).  Does not synchronise. */
+int eesd_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
 /* Launch-shape knobs for benchmark sweeps (process-wide; 0 restores the built-in heuristic):
  * "valu_nw", "valu_tpw", "valu_rp", "mfma_nw", "mfma_ksplit", "mfma_tile", "attn_split", "mfma_min_m". */
 int eesd_set_tunable(const char* name, int value);

@@ -75,7 +75,7 @@ _LIB = None
 EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_rollback",
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
-           "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
+           "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
 
 
 def lib() -> C.CDLL:
@@ -109,6 +109,7 @@ def lib() -> C.CDLL:
     L.eesd_set_tunable.argtypes = [C.c_char_p, C.c_int]
     L.eesd_debug_profile_begin.argtypes = [VP, I32, I32, I32]
     L.eesd_debug_profile_end.argtypes = [VP, P(I32), P(C.c_double)]
+    L.eesd_debug_copy.argtypes = [VP, VP, C.c_size_t, VP]
     L.eesd_op_accept.argtypes = [VP, VP, VP, P(C.c_double), I32, I32, I32, VP, P(I32)]
     L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
     L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, VP]
@@ -293,6 +294,12 @@ def op_softmax_sample(logits, probs, temperature: float, u: float, stream: int =
     if rc:
         raise EesdError(rc, "eesd_op_softmax_sample")
     return tok.value
+
+
+def calibration_copy(dst, src, stream: int = 0) -> None:
+    rc = lib().eesd_debug_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), C.c_void_p(stream))
+    if rc:
+        raise EesdError(rc, "eesd_debug_copy")
 
 
 def op_gemm(W, X, Y, path: int = GEMM_AUTO, stream: int = 0) -> None:

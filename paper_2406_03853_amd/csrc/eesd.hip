@@ -274,7 +274,7 @@ static bool pick_mfma(const eesd_ctx* c, int M) {
 template <int EPI>
 static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
     bool prof = c->prof_family == (mfma ? 1 : 0) && c->prof_epi == EPI && (c->prof_in == 0 || c->prof_in == p.in_dim) &&
-                c->prof_used < PROF_MAX_PAIRS;
+                p.M <= MAX_ROWS && c->prof_used < PROF_MAX_PAIRS;   // decoding passes only, not prefill blocks
     if (prof) {
         while (c->prof_ev.size() < 2 * (c->prof_used + 1)) {
             hipEvent_t e;
@@ -1114,6 +1114,20 @@ extern "C" int eesd_debug_read(eesd_ctx* c, int what, int index, int32_t n_token
         }
     }
     return fail(c, EESD_EINVAL, "debug_read: unknown selector %d", what);
+}
+
+// plain streaming copy with a name of its own, so that a hardware-counter run can be scaled by a
+// kernel whose HBM traffic is known exactly (n bytes read, n bytes written)
+__global__ void eesd_calibration_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+extern "C" int eesd_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+    if (!dst || !src || bytes % 16) return EESD_EINVAL;
+    hipLaunchKernelGGL(eesd_calibration_copy_kernel, dim3(4096), dim3(256), 0, (hipStream_t)hip_stream, (const uint4*)src, (uint4*)dst, bytes / 16);
+    return hipGetLastError() == hipSuccess ? EESD_OK : EESD_EDEVICE;
 }
 
 extern "C" int eesd_debug_profile_begin(eesd_ctx* c, int32_t family, int32_t epilogue_kind, int32_t in_dim) {
