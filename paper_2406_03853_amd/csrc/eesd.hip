@@ -243,10 +243,17 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
     const int n_tiles = p.out_rows / 16, steps = p.in_dim / 128;
     int nw = g_mfma_nw;
     if (!nw) {
-        // 2-4 thousand waves over the chip, at least two 128-column steps per wave
-        nw = 2;
-        while (nw < 4 && n_tiles * ksplit * nw < 2560 && steps / (ksplit * nw * 2) >= 2) nw *= 2;
-        if (steps / ksplit < 2) nw = 1;
+        if (EPI == EPI_RESID && p.y_partial) {
+            // K is already split over workgroups: 2-4 waves each, at least two 128-column steps per wave
+            nw = 2;
+            while (nw < 4 && n_tiles * ksplit * nw < 2560 && steps / (ksplit * nw * 2) >= 2) nw *= 2;
+            if (steps / ksplit < 2) nw = 1;
+        } else {
+            // one workgroup per tile: many waves per tile keep the tail short when tiles / CU is
+            // small or fractional (measured best at 8 for the QKV, gate/up and head products)
+            nw = 8;
+            while (nw > 1 && steps / nw < 4) nw >>= 1;
+        }
     }
     nw = std::max(1, std::min(nw, 16));
     size_t lds = (size_t)nw * 64 * 16;
