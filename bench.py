@@ -80,6 +80,34 @@ def cpu_baseline(w_gpu, shape, temperature, mean_k, mean_commit, si):
                 draft_step_s=t_draft_full, verify_s=t_verify_full)
 
 
+def latency_sweep(ctx, torch, cache_tokens, k_cap, b_draft, shape, si):
+    """Draft-step and verify-pass latency for fixed K over a cache of `cache_tokens` positions
+    (filled with a deterministic pattern: attention cost depends on the shape only)."""
+    res = {}
+    L = shape["n_layers"]
+    for K in [k for k in (0, 1, 2, 3, 5, 7, 10, 15) if k <= k_cap]:
+        ctx.fill_cache(cache_tokens, 1)
+        td = tv = 0.0
+        reps = 5
+        for r in range(reps + 1):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            ev[0].record()
+            for _ in range(K):
+                ctx.draft_step(sync=False)
+            ev[1].record()
+            ctx.verify()
+            ev[2].record()
+            ctx.accept()
+            ctx.rollback(0)
+            if r:
+                td += ev[0].elapsed_time(ev[1])
+                tv += ev[1].elapsed_time(ev[2])
+        b_verify = pass_bytes(shape, L, True, cache_tokens, si)
+        res[str(K)] = {"verify_rows": K + 1, "verify_ms": tv / reps, "verify_GBps": b_verify / (tv / reps * 1e-3) / 1e9,
+                       "draft_step_ms": (td / reps / K) if K else None}
+    return res
+
+
 def stored_traffic(workload):
     """HBM bytes per launch of the dominant kernel from the committed hardware-counter summary
     (profiles/hbm_traffic.json, written from two rocprofv3 --pmc runs), or None."""
@@ -98,6 +126,8 @@ def main():
     ap.add_argument("--workload", default="70b", choices=sorted(WORKLOADS))
     ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--latency-sweep", action="store_true",
+                    help="also report draft-step and verify-pass latency versus K over a pre-filled cache (outside the timed region)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's 1 GiB copy kernel a few times (reference for hardware-counter runs)")
     args = ap.parse_args()
@@ -121,6 +151,9 @@ def main():
     torch.cuda.synchronize()
     t_weights = time.perf_counter() - t0
     max_seq = n_prompt + max_new + k_cap + 2
+    sweep_tokens = 2048 if args.workload == "70b" else n_prompt       # cache length of the latency sweep
+    if args.latency_sweep:
+        max_seq = max(max_seq, sweep_tokens + k_cap + 2)
     max_seq = (max_seq + 63) // 64 * 64
     ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64)
     prompt = si.make_prompt(n_prompt, shape["vocab"], 0)
@@ -187,6 +220,8 @@ def main():
                    "mean_K": mean_k, "tokens_per_round": mean_commit, "v_d": st.v_d, "r_d": st.r_d, "hm": st.hm,
                    "ts_alpha": st.alpha, "ts_beta": st.beta, "weight_init_s": t_weights},
     }
+    if args.latency_sweep:
+        out["latency_vs_K"] = latency_sweep(ctx, torch, sweep_tokens, k_cap, b_draft, shape, si)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, shape, args.temperature, mean_k, mean_commit, si)
     print(json.dumps(out))

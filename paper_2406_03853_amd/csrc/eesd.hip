@@ -31,7 +31,7 @@ static int g_valu_rp = 0;      // row pairs per task (1 or 2)
 static int g_mfma_ksplit = 0;  // cross-workgroup K split of the residual products (0 = heuristic)
 static int g_mfma_nw = 0;      // waves per workgroup of the MFMA product
 static int g_attn_split = 0;   // keys per attention split
-static int g_mfma_tile = 0;    // 1: blocks of <= 16 rows also take the LDS-shared tile kernel
+static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: from 9 rows on
 static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
 
 extern "C" int eesd_set_tunable(const char* name, int value) {
@@ -218,12 +218,13 @@ static int mfma_ksplit(int out_rows, int in_dim) {
     return ks;
 }
 
-static bool tile_shape_ok(int out_rows, int in_dim) { return (out_rows / 16) % 4 == 0 && in_dim % GT_KC == 0; }
+#define GT_KC_MIN 256
+static bool tile_shape_ok(int out_rows, int in_dim) { return (out_rows / 16) % 4 == 0 && in_dim % GT_KC_MIN == 0; }
 
-template <int EPI, int NB>
+template <int EPI, int NB, int KC>
 static hipError_t launch_tile_t(const GemmP& p, int ksplit, hipStream_t st) {
-    size_t lds = (size_t)NB * 16 * GT_RS * sizeof(bf16_t);
-    auto fn = gemm_tile_kernel<EPI, NB>;
+    size_t lds = (size_t)2 * NB * 16 * (KC + GT_PAD) * sizeof(bf16_t);
+    auto fn = gemm_tile_kernel<EPI, NB, KC>;
     hipError_t e = allow_lds((const void*)fn, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, dim3(p.out_rows / 64, ksplit), dim3(256), lds, st, p);
@@ -232,11 +233,17 @@ static hipError_t launch_tile_t(const GemmP& p, int ksplit, hipStream_t st) {
 
 template <int EPI>
 static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
-    if ((p.M > 16 || g_mfma_tile) && tile_shape_ok(p.out_rows, p.in_dim)) {
-        if (p.M <= 16) return launch_tile_t<EPI, 1>(p, ksplit, st);
-        if (p.M <= 32) return launch_tile_t<EPI, 2>(p, ksplit, st);
-        if (p.M <= 64) return launch_tile_t<EPI, 4>(p, ksplit, st);
-        if (p.M <= 128) return launch_tile_t<EPI, 8>(p, ksplit, st);
+    // Blocks of up to 8 rows stream fastest with one workgroup per tile; from about 9 rows on the
+    // activation operand traffic of that form costs more than the tile kernel's barriers (measured
+    // crossover: 7 rows at the 13B shape, 10 at the 70B shape).
+    if ((p.M > 8 || g_mfma_tile == 1) && g_mfma_tile != 2 && tile_shape_ok(p.out_rows, p.in_dim) || (p.M > 16 && tile_shape_ok(p.out_rows, p.in_dim))) {
+        // verify-sized blocks take 512-column chunks when K allows (fewer barriers); the wide prefill
+        // blocks keep 256 so that two activation buffers fit in LDS
+        if (p.M <= 16) return (p.in_dim / ksplit) % 512 == 0 && p.in_dim % 512 == 0 ? launch_tile_t<EPI, 1, 512>(p, ksplit, st)
+                                                                                     : launch_tile_t<EPI, 1, 256>(p, ksplit, st);
+        if (p.M <= 32) return launch_tile_t<EPI, 2, 256>(p, ksplit, st);
+        if (p.M <= 64) return launch_tile_t<EPI, 4, 256>(p, ksplit, st);
+        if (p.M <= 128) return launch_tile_t<EPI, 8, 256>(p, ksplit, st);
         return hipErrorInvalidValue;
     }
     if (p.M > 16) return hipErrorInvalidValue;
@@ -772,6 +779,12 @@ extern "C" int eesd_get_stats(const eesd_ctx* c, eesd_stats* out) {
 // ---------------------------------------------------------------------------------------------
 // the calls of a round
 // ---------------------------------------------------------------------------------------------
+// the sampling kernels keep a vocabulary row in LDS when it fits
+static int smp_use_lds(int V) { return V <= SMP_LDS_MAX_V; }
+static size_t smp_lds_bytes(int V) { return smp_use_lds(V) ? (size_t)V * sizeof(float) : 0; }
+template <typename F>
+static hipError_t smp_allow(F fn, int V) { return allow_lds((const void*)fn, smp_lds_bytes(V)); }
+
 static float inv_temperature(const eesd_ctx* c) { return c->cfg.temperature > 0.f ? 1.0f / c->cfg.temperature : 1.0f; }
 static int greedy(const eesd_ctx* c) { return c->cfg.temperature == 0.f; }
 
@@ -810,8 +823,9 @@ extern "C" int eesd_prefill(eesd_ctx* c, const int32_t* prompt, int32_t n, int32
     rc = run_head(c, c->w.final_norm, c->w.lm_head, last_m - 1, 1, c->logits, last_mfma);
     if (rc) return rc;
     double u = uniform53(g.seed, STREAM_RESAMPLE, 0, 0, 0);
-    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, c->logits, c->p_rows, g.vocab, inv_temperature(c),
-                       greedy(c), u, -1, c->blk_tok);
+    HIP_TRY(c, smp_allow(softmax_sample_kernel, g.vocab));
+    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, c->logits, c->p_rows, g.vocab,
+                       inv_temperature(c), greedy(c), u, -1, c->blk_tok, smp_use_lds(g.vocab));
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipMemcpyAsync(c->h_result, c->blk_tok, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -847,8 +861,10 @@ extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
     int forced = -1;
     if (c->forced_pos < c->forced.size()) forced = c->forced[c->forced_pos++];
     double u = uniform53(g.seed, STREAM_DRAFT, c->round, i, 0);
-    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, ql, c->q_rows + (size_t)i * g.vocab, g.vocab,
-                       inv_temperature(c), greedy(c), u, forced, c->blk_tok + i + 1);
+    HIP_TRY(c, smp_allow(softmax_sample_kernel, g.vocab));
+    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, ql,
+                       c->q_rows + (size_t)i * g.vocab, g.vocab, inv_temperature(c), greedy(c), u, forced, c->blk_tok + i + 1,
+                       smp_use_lds(g.vocab));
     HIP_TRY(c, hipGetLastError());
     c->n_drafted = i + 1;
     if (tok_or_null) {
@@ -886,8 +902,9 @@ extern "C" int eesd_accept(eesd_ctx* c, const double* uniforms_or_null, int32_t*
     uu.u[K] = uniforms_or_null ? uniforms_or_null[K] : uniform53(g.seed, STREAM_RESAMPLE, c->round, 0, 0);
     for (int i = 0; i <= K; ++i)
         if (!(uu.u[i] >= 0.0 && uu.u[i] < 1.0)) return fail(c, EESD_EINVAL, "accept: uniform %d outside [0,1)", i);
-    hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, c->logits, c->p_rows, c->q_rows, c->blk_tok + 1, K, g.vocab,
-                       inv_temperature(c), greedy(c), 1, uu, c->result_dev, c->blk_tok);
+    HIP_TRY(c, smp_allow(accept_kernel, g.vocab));
+    hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, c->logits, c->p_rows, c->q_rows,
+                       c->blk_tok + 1, K, g.vocab, inv_temperature(c), greedy(c), 1, uu, c->result_dev, c->blk_tok, smp_use_lds(g.vocab));
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipMemcpyAsync(c->h_result, c->result_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1176,7 +1193,7 @@ extern "C" int eesd_op_accept(const float* p_rows, const float* q_rows, const in
     int32_t* d_res = nullptr;
     if (hipMalloc((void**)&d_res, 2 * sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
     hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(SMP_THREADS), 0, st, (const float*)nullptr, const_cast<float*>(p_rows), q_rows, drafts, K,
-                       vocab, 1.0f, greedy_flag, 0, uu, d_res, (int32_t*)nullptr);
+                       vocab, 1.0f, greedy_flag, 0, uu, d_res, (int32_t*)nullptr, 0);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e == hipSuccess) e = hipMemcpy(result, d_res, 2 * sizeof(int32_t), hipMemcpyDeviceToHost);
@@ -1191,9 +1208,12 @@ extern "C" int eesd_op_softmax_sample(const float* logits, float* probs, int32_t
     hipStream_t st = (hipStream_t)hip_stream;
     int32_t* d_tok = nullptr;
     if (hipMalloc((void**)&d_tok, sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
-    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), 0, st, logits, probs, vocab, temperature > 0.f ? 1.0f / temperature : 1.0f,
-                       temperature == 0.f, u, -1, d_tok);
-    hipError_t e = hipGetLastError();
+    hipError_t e = smp_allow(softmax_sample_kernel, vocab);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(vocab), st, logits, probs, vocab,
+                           temperature > 0.f ? 1.0f / temperature : 1.0f, temperature == 0.f, u, -1, d_tok, smp_use_lds(vocab));
+        e = hipGetLastError();
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e == hipSuccess) e = hipMemcpy(token, d_tok, sizeof(int32_t), hipMemcpyDeviceToHost);
     hipFree(d_tok);

@@ -23,10 +23,11 @@ def tol_of(shape: dict) -> float:
     return TOL_BF16 if shape["dtype"] == "bf16" else TOL_F32
 
 
-def make_pair(shape, wseed, max_seq, temperature, k_cap=5, jitter=0.1, gamma=None, **kw):
-    """The same weights for the oracle (numpy, CPU) and the library (torch, GPU)."""
+def make_pair(shape, wseed, max_seq, temperature, k_cap=5, jitter=0.1, gamma=None, gen_device="cpu", **kw):
+    """The same weights for the oracle (numpy, CPU) and the library (torch, GPU).
+    gen_device="cuda" draws big models on the GPU and copies them to the host for the oracle."""
     import paper_2406_03853_amd as pk
-    w = si.make_weights(shape, seed=wseed, norm_gain_jitter=jitter, correlated_draft=gamma)
+    w = si.make_weights(shape, seed=wseed, norm_gain_jitter=jitter, correlated_draft=gamma, device=gen_device)
     o = orc.OracleEESD(si.weights_to_numpy(w), max_seq, temperature, seed=kw.get("seed", 0), k_cap=k_cap,
                        ts_update="literal" if kw.get("ts_update", 0) else "prose")
     g = pk.EESD(si.weights_to_device(w, "cuda"), max_seq, temperature, k_cap=k_cap, **kw)
