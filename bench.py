@@ -207,7 +207,7 @@ def main():
         "config": {"workload": f"full EESD generation, {shape['name']} (L={L}, N={N}), random weights seed {wseed}, "
                                f"prompt {n_prompt} uniform ids, {max_new} new tokens, Beta-TS K cap {k_cap}, "
                                f"temperature {args.temperature:g}, batch 1",
-                   "prefill": "included in every step (128-row blocks, tiled MFMA product)"},
+                   "prefill": "included in every step (128-row blocks, tiled MFMA product)" if bf16 else "included in every step (16-row blocks)"},
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<SWIGLU> (gate/up product of verify and prefill blocks)" if bf16
                      else "gemm_valu_kernel<SWIGLU>",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

@@ -295,3 +295,45 @@ def test_call_order_and_range_errors():
     with pytest.raises(pk.EesdError) as e:
         g.generate([1] * 40, 30)
     assert e.value.code == -4
+
+
+def test_controller_with_non_integer_prior_is_statistically_right():
+    """Beta draws for non-integer parameters (gamma ratios) have no bit-exact counterpart in the
+    oracle; pin them through the law of K: P(K >= 2) = E[theta] = alpha / (alpha + beta), truncated
+    geometric beyond (conjugacy, Section 3.3)."""
+    require_gpu()
+    from scipy import stats
+    import paper_2406_03853_amd as pk
+    w = si.weights_to_device(si.make_weights(si.TINY, seed=0), "cuda")
+    a0, b0, cap, n = 2.5, 1.5, 5, 300
+    ks = []
+    for seed in range(n):
+        g = pk.EESD(w, 64, 1.0, seed=seed, k_cap=cap, alpha0=a0, beta0=b0)
+        g.prefill([1, 2, 3])
+        ks.append(g.next_draft_len(cap))
+        g.close()
+    ks = np.array(ks)
+    assert ks.min() >= 1 and ks.max() <= cap
+    # K = 1 + number of leading chi = 1; theta is redrawn for every chi, so the draws are i.i.d. Bernoulli(E theta)
+    c = a0 / (a0 + b0)
+    want = np.array([c ** (k - 1) * (1 - c) for k in range(1, cap)] + [c ** (cap - 1)])
+    got = np.bincount(ks, minlength=cap + 1)[1:]
+    assert stats.chisquare(got, want * n).pvalue > 1e-3
+
+
+def test_schedule_and_fixed_controller_modes():
+    require_gpu()
+    import paper_2406_03853_amd as pk
+    w = si.weights_to_device(si.make_weights(si.TINY, seed=0), "cuda")
+    g = pk.EESD(w, 128, 1.0, k_cap=5, ts_mode=pk.TS_SCHEDULE)
+    g.set_draft_schedule([3, 1, 5, 2])
+    out, st = g.generate(si.make_prompt(8, 512, 1), 40)
+    assert len(out) == 40 and st.drafted <= 5 * st.rounds
+    g2 = pk.EESD(w, 128, 1.0, k_cap=4, ts_mode=pk.TS_FIXED)
+    out2, st2 = g2.generate(si.make_prompt(8, 512, 1), 40)
+    # every round drafts k_cap tokens except possibly the last ones, which are clipped to what is still wanted
+    assert st2.drafted <= 4 * st2.rounds and st2.drafted >= 4 * (st2.rounds - 2)
+    with pytest.raises(pk.EesdError):
+        g.set_draft_schedule([0, 2])
+    with pytest.raises(pk.EesdError):
+        g.set_draft_schedule([9])
