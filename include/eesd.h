@@ -179,6 +179,17 @@ int eesd_set_draft_schedule(eesd_ctx* ctx, const int32_t* k_per_round, int32_t n
  * exactly as eesd_generate does). */
 int eesd_next_draft_len(eesd_ctx* ctx, int32_t k_max, int32_t* k_out);
 
+/* ---- host-only pieces (no device needed) ------------------------------------------------- */
+/* The counter-based uniform of (seed, stream, round, slot, sub): top 53 bits of the splitmix64
+ * output function of the packed key, times 2^-53.  Streams: 1 draft, 2 accept, 3 resample,
+ * 4 controller theta, 5 controller chi. */
+double eesd_host_uniform(uint64_t seed, int32_t stream, int64_t round, int32_t slot, int32_t sub);
+/* K that Algorithm 2 (steps 5-14) draws for `round` from the posterior Beta(alpha, beta), at most
+ * k_max.  Returns K >= 1, or EESD_EINVAL. */
+int eesd_host_draw_k(double alpha, double beta, uint64_t seed, int64_t round, int32_t k_max);
+/* Posterior update of Eq. 3-4 in place (reading as eesd_config.ts_update). */
+int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t n_drafted, int32_t reading);
+
 /* ---- test and benchmark hooks ------------------------------------------------------- */
 enum {
     EESD_READ_DRAFT_LOGITS = 0,  /* index = draft slot i (0-based): vocab floats */

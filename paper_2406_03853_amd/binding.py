@@ -75,7 +75,7 @@ _LIB = None
 EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_rollback",
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
-           "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
+           "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
 
 
 def lib() -> C.CDLL:
@@ -110,11 +110,15 @@ def lib() -> C.CDLL:
     L.eesd_debug_profile_begin.argtypes = [VP, I32, I32, I32]
     L.eesd_debug_profile_end.argtypes = [VP, P(I32), P(C.c_double)]
     L.eesd_debug_copy.argtypes = [VP, VP, C.c_size_t, VP]
+    L.eesd_host_uniform.argtypes = [C.c_uint64, I32, C.c_int64, I32, I32]
+    L.eesd_host_uniform.restype = C.c_double
+    L.eesd_host_draw_k.argtypes = [C.c_double, C.c_double, C.c_uint64, C.c_int64, I32]
+    L.eesd_host_ts_update.argtypes = [P(C.c_double), P(C.c_double), I32, I32, I32]
     L.eesd_op_accept.argtypes = [VP, VP, VP, P(C.c_double), I32, I32, I32, VP, P(I32)]
     L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
     L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, VP]
     for name in EXPORTS:
-        if name not in ("eesd_destroy", "eesd_last_error"):
+        if name not in ("eesd_destroy", "eesd_last_error", "eesd_host_uniform"):
             getattr(L, name).restype = C.c_int
     _LIB = L
     return L
@@ -126,6 +130,25 @@ def _i32(a) -> np.ndarray:
 
 def _ptr(arr: np.ndarray, ct):
     return arr.ctypes.data_as(C.POINTER(ct))
+
+
+def host_uniform(seed: int, stream: int, rnd: int, slot: int = 0, sub: int = 0) -> float:
+    return lib().eesd_host_uniform(seed, stream, rnd, slot, sub)
+
+
+def host_draw_k(alpha: float, beta: float, seed: int, rnd: int, k_max: int) -> int:
+    k = lib().eesd_host_draw_k(alpha, beta, seed, rnd, k_max)
+    if k < 1:
+        raise EesdError(k, "eesd_host_draw_k")
+    return k
+
+
+def host_ts_update(alpha: float, beta: float, n_accepted: int, n_drafted: int, reading: int = 0):
+    a, b = C.c_double(alpha), C.c_double(beta)
+    rc = lib().eesd_host_ts_update(C.byref(a), C.byref(b), n_accepted, n_drafted, reading)
+    if rc:
+        raise EesdError(rc, "eesd_host_ts_update")
+    return a.value, b.value
 
 
 def set_tunable(name: str, value: int) -> None:

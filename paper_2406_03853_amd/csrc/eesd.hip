@@ -558,18 +558,40 @@ static double gamma_mt(double shape, uint64_t seed, int64_t rnd, int slot, int& 
     }
 }
 
-static double beta_draw(const eesd_ctx* c, int slot) {
-    const double a = c->alpha, b = c->beta;
+static double beta_draw_at(double a, double b, uint64_t seed, int64_t rnd, int slot) {
     if (a == floor(a) && b == floor(b) && a + b < 1e6) {
         int ia = (int)a, n = (int)(a + b) - 1;
         std::vector<double> us(n);
-        for (int j = 0; j < n; ++j) us[j] = uniform53(c->cfg.seed, STREAM_TS_THETA, c->round, slot, j);
+        for (int j = 0; j < n; ++j) us[j] = uniform53(seed, STREAM_TS_THETA, rnd, slot, j);
         std::nth_element(us.begin(), us.begin() + (ia - 1), us.end());
         return us[ia - 1];
     }
     int sub = 0;
-    double x = gamma_mt(a, c->cfg.seed, c->round, slot, sub), y = gamma_mt(b, c->cfg.seed, c->round, slot, sub);
+    double x = gamma_mt(a, seed, rnd, slot, sub), y = gamma_mt(b, seed, rnd, slot, sub);
     return x / (x + y);
+}
+
+// Algorithm 2, steps 5-14 for one round: draft, draw theta from the posterior the round starts
+// with, draw chi ~ Bernoulli(theta), stop on chi = 0 or at k_max drafts.
+static int beta_ts_draw_k(double alpha, double beta, uint64_t seed, int64_t rnd, int k_max) {
+    if (k_max < 1) k_max = 1;
+    int k = 0;
+    for (;;) {
+        ++k;                                  // draft token k
+        if (k >= k_max) return k_max;
+        double theta = beta_draw_at(alpha, beta, seed, rnd, k);
+        bool chi = uniform53(seed, STREAM_TS_CHI, rnd, k, 0) < theta;
+        if (!chi) return k;
+    }
+}
+
+// Eq. 3-4: alpha += r, beta += n - r (the two readings of n differ, see eesd_config.ts_update)
+static void beta_ts_update(double* alpha, double* beta, int a, int K, int reading) {
+    if (K < 1) return;
+    int r = a;
+    int n = reading == 0 ? std::min(a + 1, K) : std::min(a + 2, K);
+    *alpha += r;
+    *beta += n - r;
 }
 
 // K of the coming round.  Every theta of a round is drawn from the posterior the round starts
@@ -583,22 +605,24 @@ static int draw_k(eesd_ctx* c, int k_max) {
         ++c->sched_round;
         return std::max(1, std::min(k, k_max));
     }
-    int k = 0;
-    for (;;) {
-        ++k;                                  // draft token k
-        if (k >= k_max) return k_max;
-        double theta = beta_draw(c, k);
-        bool chi = uniform53(c->cfg.seed, STREAM_TS_CHI, c->round, k, 0) < theta;
-        if (!chi) return k;
-    }
+    return beta_ts_draw_k(c->alpha, c->beta, c->cfg.seed, c->round, k_max);
 }
 
-static void ts_update(eesd_ctx* c, int a, int K) {
-    if (K < 1) return;
-    int r = a;
-    int n = c->cfg.ts_update == 0 ? std::min(a + 1, K) : std::min(a + 2, K);
-    c->alpha += r;
-    c->beta += n - r;
+static void ts_update(eesd_ctx* c, int a, int K) { beta_ts_update(&c->alpha, &c->beta, a, K, c->cfg.ts_update); }
+
+// Host-only entry points (no GPU needed): the controller and the uniform generator as the
+// library uses them, so that they can be checked without a device.
+extern "C" double eesd_host_uniform(uint64_t seed, int32_t stream, int64_t round, int32_t slot, int32_t sub) {
+    return uniform53(seed, stream, round, slot, sub);
+}
+extern "C" int eesd_host_draw_k(double alpha, double beta, uint64_t seed, int64_t round, int32_t k_max) {
+    if (!(alpha > 0.0) || !(beta > 0.0)) return EESD_EINVAL;
+    return beta_ts_draw_k(alpha, beta, seed, round, k_max);
+}
+extern "C" int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t n_drafted, int32_t reading) {
+    if (!alpha || !beta || n_accepted < 0 || n_accepted > n_drafted || reading < 0 || reading > 1) return EESD_EINVAL;
+    beta_ts_update(alpha, beta, n_accepted, n_drafted, reading);
+    return EESD_OK;
 }
 
 static void finish_stats(eesd_ctx* c) {

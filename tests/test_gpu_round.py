@@ -337,3 +337,53 @@ def test_schedule_and_fixed_controller_modes():
         g.set_draft_schedule([0, 2])
     with pytest.raises(pk.EesdError):
         g.set_draft_schedule([9])
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_same_seed_twice_is_bit_identical(name):
+    """No atomics in any reduction: two runs give the same bits (tokens and logits)."""
+    require_gpu()
+    shape = SHAPES[name]
+    runs = []
+    for _ in range(2):
+        _, g = make_pair(shape, 13, 160, 1.0, k_cap=5, seed=21)
+        out, st = g.generate(si.make_prompt(45, shape["vocab"], 2), 40)
+        g.verify()                      # one more plain target step to look at logits
+        runs.append((out, st.drafted, st.accepted, g.verify_logits(0).copy()))
+    assert runs[0][0] == runs[1][0] and runs[0][1:3] == runs[1][1:3]
+    assert np.array_equal(runs[0][3], runs[1][3])
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_edge_sizes(name):
+    """One-token prompt, the largest block (k_cap = 15: 16 verify rows), a cache filled to its last
+    position, a single new token."""
+    require_gpu()
+    import paper_2406_03853_amd as pk
+    shape = SHAPES[name]
+    tol = tol_of(shape)
+    o, g = make_pair(shape, 17, 64, 1.0, k_cap=15, ts_mode=pk.TS_FIXED)
+    t_ref = o.prefill([7])
+    g.prefill([7])
+    assert rel_err(g.verify_logits(0), o.prefill_logits) < tol
+    g.force_pending(t_ref)
+    ds = [o.draft_step() for _ in range(15)]
+    g.force_drafts(ds)
+    for _ in range(15):
+        g.draft_step(sync=False)
+    p_logits = o.verify()
+    g.verify()
+    for i in (0, 7, 15):
+        assert rel_err(g.verify_logits(i), p_logits[i]) < tol
+    a, y = o.accept()
+    g.accept()
+    o.rollback(a, y)
+    g.rollback(a)
+    # single new token / exact fit of max_seq
+    _, g2 = make_pair(shape, 17, 64, 0.0, k_cap=3)
+    out, st = g2.generate(si.make_prompt(10, shape["vocab"], 1), 1)
+    assert len(out) == 1 and st.rounds == 0
+    out, st = g2.generate(si.make_prompt(10, shape["vocab"], 1), 64 - 10 - 3 - 1)
+    assert len(out) == 50
+    with pytest.raises(pk.EesdError):
+        g2.generate(si.make_prompt(10, shape["vocab"], 1), 51)

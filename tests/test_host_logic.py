@@ -1,0 +1,48 @@
+"""Host-side logic of the library against the oracle, without a GPU: the counter-based uniforms,
+the Beta-posterior controller of Section 3.3 / Algorithm 2 (bit-exact for integer posteriors) and
+the posterior update of Eq. 3-4 in both readings."""
+import numpy as np
+import pytest
+
+import paper_2406_03853_amd as pk
+from oracle import eesd_oracle as orc
+
+
+def test_uniforms_are_bit_identical_to_the_oracles():
+    for seed in (0, 1, 0xDEADBEEFCAFE, 2 ** 63 + 5):
+        for stream in (1, 2, 3, 4, 5):
+            for rnd in (0, 1, 77, 65535, 2 ** 20 + 3):
+                for slot, sub in ((0, 0), (3, 0), (15, 1), (200, 4097)):
+                    assert pk.host_uniform(seed, stream, rnd, slot, sub) == orc.uniform(seed, stream, rnd, slot, sub)
+
+
+def test_draft_length_draws_are_bit_identical_for_integer_posteriors():
+    for a, b in ((1, 1), (3, 2), (2, 9), (40, 17), (1, 300)):
+        for seed in (0, 9):
+            ts = orc.BetaTS(a, b, seed)
+            for rnd in range(1, 120):
+                for k_max in (1, 2, 5, 10):
+                    assert pk.host_draw_k(a, b, seed, rnd, k_max) == ts.draw_k(rnd, k_max), (a, b, seed, rnd, k_max)
+
+
+def test_posterior_update_matches_both_readings():
+    for mode, reading in (("prose", 0), ("literal", 1)):
+        for K in range(1, 8):
+            for a in range(0, K + 1):
+                ts = orc.BetaTS(2, 3, 0, mode)
+                ts.update(a, K)
+                assert pk.host_ts_update(2.0, 3.0, a, K, reading) == (ts.alpha, ts.beta)
+    with pytest.raises(pk.EesdError):
+        pk.host_ts_update(1.0, 1.0, 5, 4, 0)
+
+
+def test_non_integer_posterior_keeps_the_law_of_k():
+    from scipy import stats
+    a, b, cap, n = 2.5, 1.5, 6, 4000
+    ks = np.array([pk.host_draw_k(a, b, 3, rnd, cap) for rnd in range(n)])
+    c = a / (a + b)
+    want = np.array([c ** (k - 1) * (1 - c) for k in range(1, cap)] + [c ** (cap - 1)])
+    got = np.bincount(ks, minlength=cap + 1)[1:]
+    assert stats.chisquare(got, want * n).pvalue > 1e-3
+    with pytest.raises(pk.EesdError):
+        pk.host_draw_k(0.0, 1.0, 0, 0, 4)
