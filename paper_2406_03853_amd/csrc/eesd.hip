@@ -31,14 +31,16 @@ static int g_valu_rp = 0;      // row pairs per task (1 or 2)
 static int g_mfma_ksplit = 0;  // cross-workgroup K split of the residual products (0 = heuristic)
 static int g_mfma_nw = 0;      // waves per workgroup of the MFMA product
 static int g_attn_split = 0;   // keys per attention split
-static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: from 9 rows on
+static int g_tile_kc = 0;      // 512: the tile kernel takes 512-column chunks for verify-sized blocks (default 256)
+static int g_tile_nwt = 0;     // 4 / 8: tiles per workgroup of the tile kernel for verify-sized blocks (0 = by tile count)
+static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: by rows and tile count
 static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
 
 extern "C" int eesd_set_tunable(const char* name, int value) {
     if (!name) return EESD_EINVAL;
     struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
                                              {"mfma_ksplit", &g_mfma_ksplit}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
-                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}};
+                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
     for (auto& e : t)
         if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
     return EESD_EINVAL;
@@ -221,29 +223,38 @@ static int mfma_ksplit(int out_rows, int in_dim) {
 #define GT_KC_MIN 256
 static bool tile_shape_ok(int out_rows, int in_dim) { return (out_rows / 16) % 4 == 0 && in_dim % GT_KC_MIN == 0; }
 
-template <int EPI, int NB, int KC>
+template <int EPI, int NB, int KC, int NWT>
 static hipError_t launch_tile_t(const GemmP& p, int ksplit, hipStream_t st) {
     size_t lds = (size_t)2 * NB * 16 * (KC + GT_PAD) * sizeof(bf16_t);
-    auto fn = gemm_tile_kernel<EPI, NB, KC>;
+    auto fn = gemm_tile_kernel<EPI, NB, KC, NWT>;
     hipError_t e = allow_lds((const void*)fn, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, dim3(p.out_rows / 64, ksplit), dim3(256), lds, st, p);
+    hipLaunchKernelGGL(fn, dim3(p.out_rows / (16 * NWT), ksplit), dim3(64 * NWT), lds, st, p);
     return hipGetLastError();
 }
 
 template <int EPI>
 static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
-    // Blocks of up to 8 rows stream fastest with one workgroup per tile; from about 9 rows on the
-    // activation operand traffic of that form costs more than the tile kernel's barriers (measured
-    // crossover: 7 rows at the 13B shape, 10 at the 70B shape).
-    if ((p.M > 8 || g_mfma_tile == 1) && g_mfma_tile != 2 && tile_shape_ok(p.out_rows, p.in_dim) || (p.M > 16 && tile_shape_ok(p.out_rows, p.in_dim))) {
-        // verify-sized blocks take 512-column chunks when K allows (fewer barriers); the wide prefill
-        // blocks keep 256 so that two activation buffers fit in LDS
-        if (p.M <= 16) return (p.in_dim / ksplit) % 512 == 0 && p.in_dim % 512 == 0 ? launch_tile_t<EPI, 1, 512>(p, ksplit, st)
-                                                                                     : launch_tile_t<EPI, 1, 256>(p, ksplit, st);
-        if (p.M <= 32) return launch_tile_t<EPI, 2, 256>(p, ksplit, st);
-        if (p.M <= 64) return launch_tile_t<EPI, 4, 256>(p, ksplit, st);
-        if (p.M <= 128) return launch_tile_t<EPI, 8, 256>(p, ksplit, st);
+    // Which kernel (measured per product at the 13B and 70B shapes): one workgroup per tile streams
+    // fastest for few rows and for the products with few tiles (QKV, attention output, FFN down) at
+    // any M <= 16; from about 6 rows on the products with many tiles (gate/up, LM heads) gain more
+    // from sharing the activation operand through LDS than they lose to its barriers, with 8 tiles
+    // per workgroup when there are very many.  Prefill blocks (M > 16) always take the tile kernel.
+    const int n_tiles16 = p.out_rows / 16;
+    const bool partial = EPI == EPI_RESID && p.y_partial;
+    bool use_tile = p.M > 16;
+    if (p.M <= 16 && g_mfma_tile == 1) use_tile = true;
+    if (p.M <= 16 && g_mfma_tile == 0) use_tile = p.M >= 6 && n_tiles16 >= 1536 && !partial;
+    if (use_tile && tile_shape_ok(p.out_rows, p.in_dim)) {
+        if (p.M <= 16) {
+            const bool w8 = (g_tile_nwt ? g_tile_nwt == 8 : n_tiles16 >= 3072) && n_tiles16 % 8 == 0;
+            if (g_tile_kc == 512 && p.in_dim % 512 == 0)
+                return w8 ? launch_tile_t<EPI, 1, 512, 8>(p, ksplit, st) : launch_tile_t<EPI, 1, 512, 4>(p, ksplit, st);
+            return w8 ? launch_tile_t<EPI, 1, 256, 8>(p, ksplit, st) : launch_tile_t<EPI, 1, 256, 4>(p, ksplit, st);
+        }
+        if (p.M <= 32) return launch_tile_t<EPI, 2, 256, 4>(p, ksplit, st);
+        if (p.M <= 64) return launch_tile_t<EPI, 4, 256, 4>(p, ksplit, st);
+        if (p.M <= 128) return launch_tile_t<EPI, 8, 256, 4>(p, ksplit, st);
         return hipErrorInvalidValue;
     }
     if (p.M > 16) return hipErrorInvalidValue;

@@ -64,6 +64,22 @@ def test_gemm_tile_kernel_bf16(M, out, inn):
         pk.set_tunable("mfma_tile", 0)
 
 
+@pytest.mark.parametrize("kc,nwt", [(512, 4), (0, 8), (512, 8)])
+@pytest.mark.parametrize("M", [2, 11, 16])
+def test_gemm_tile_kernel_chunk_and_workgroup_shapes(kc, nwt, M):
+    require_gpu()
+    pk = _pk()
+    try:
+        pk.set_tunable("mfma_tile", 1)
+        pk.set_tunable("tile_kc", kc)
+        pk.set_tunable("tile_nwt", nwt)
+        assert _gemm_case(M, 2048, 1536, torch.bfloat16, pk.GEMM_MFMA, 8) < TOL_BF16
+        assert _gemm_case(M, 27648, 512, torch.bfloat16, pk.GEMM_MFMA, 9) < TOL_BF16
+    finally:
+        for k in ("mfma_tile", "tile_kc", "tile_nwt"):
+            pk.set_tunable(k, 0)
+
+
 @pytest.mark.parametrize("nw", [1, 2, 4, 16])
 def test_gemm_mfma_launch_shapes(nw):
     require_gpu()
