@@ -208,7 +208,7 @@ def main():
                                f"prompt {n_prompt} uniform ids, {max_new} new tokens, Beta-TS K cap {k_cap}, "
                                f"temperature {args.temperature:g}, batch 1",
                    "prefill": "included in every step (128-row blocks, tiled MFMA product)" if bf16 else "included in every step (16-row blocks)"},
-        "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<SWIGLU> (gate/up product of verify and prefill blocks)" if bf16
+        "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<SWIGLU> (gate/up product of the draft and verify passes)" if bf16
                      else "gemm_valu_kernel<SWIGLU>",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": stored_traffic(args.workload), "launches_timed": n_launch, "avg_kernel_us": avg_kernel_s * 1e6,

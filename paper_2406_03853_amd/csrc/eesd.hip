@@ -33,6 +33,7 @@ static int g_mfma_nw = 0;      // waves per workgroup of the MFMA product
 static int g_attn_split = 0;   // keys per attention split
 static int g_tile_kc = 0;      // 512: the tile kernel takes 512-column chunks for verify-sized blocks (default 256)
 static int g_tile_nwt = 0;     // 4 / 8: tiles per workgroup of the tile kernel for verify-sized blocks (0 = by tile count)
+static int g_fuse_norm = -1;   // residual -> next product hand-over without resid_norm_kernel: 1 on, 0 off, -1 by model width
 static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: by rows and tile count
 static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
 
@@ -40,7 +41,7 @@ extern "C" int eesd_set_tunable(const char* name, int value) {
     if (!name) return EESD_EINVAL;
     struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
                                              {"mfma_ksplit", &g_mfma_ksplit}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
-                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
+                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
     for (auto& e : t)
         if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
     return EESD_EINVAL;
@@ -104,7 +105,8 @@ struct eesd_ctx {
     int mapped_pages;
 
     // scratch (device)
-    float *x, *q, *attn, *act, *logits, *p_rows, *q_logits, *q_rows, *part_o, *part_ml, *rope_cs, *part;
+    float *x, *q, *attn, *act, *logits, *p_rows, *q_logits, *q_rows, *part_o, *part_ml, *rope_cs, *part, *ssq;
+    bool xb_has_ssq;       // c->xb holds gain * x (bf16) and c->ssq the partial sums of squares of x, instead of RMSNorm(x)
     bf16_t *xb, *ab, *actb;
     int32_t *blk_tok, *prompt_dev, *result_dev;
     int32_t *h_result, *h_prompt;  // pinned
@@ -245,6 +247,7 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
     bool use_tile = p.M > 16;
     if (p.M <= 16 && g_mfma_tile == 1) use_tile = true;
     if (p.M <= 16 && g_mfma_tile == 0) use_tile = p.M >= 6 && n_tiles16 >= 1536 && !partial;
+    if (EPI == EPI_RESID && p.xb_out) use_tile = false;   // the hand-over to the next product lives in the per-tile kernel
     if (use_tile && tile_shape_ok(p.out_rows, p.in_dim)) {
         if (p.M <= 16) {
             const bool w8 = (g_tile_nwt ? g_tile_nwt == 8 : n_tiles16 >= 3072) && n_tiles16 % 8 == 0;
@@ -316,6 +319,23 @@ static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
     return EESD_OK;
 }
 
+// consumers of c->xb: tell the product whether the rows still need their 1/rms
+static void take_xb(const eesd_ctx* c, GemmP& p) {
+    if (c->xb_has_ssq) {
+        p.ssq_in = c->ssq;
+        p.ssq_tiles = c->cfg.d_model / 16;
+        p.ssq_eps = c->cfg.rms_eps;
+    }
+}
+
+// a RESID product of a decoding pass that hands its rows straight to the next product
+static void fuse_next(eesd_ctx* c, GemmP& p, const void* gain) {
+    p.xb_out = c->xb;
+    p.ld_xb = c->cfg.d_model;
+    p.gain_next = gain;
+    p.ssq_out = c->ssq;
+}
+
 static GemmP gemm_base(const void* W, const void* X, int ldx, int M, int out, int in) {
     GemmP p;
     memset(&p, 0, sizeof p);
@@ -377,6 +397,7 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
 
 static int launch_rmsnorm_bf16(eesd_ctx* c, const float* x, int M, const void* gain, bf16_t* out, int ld) {
     int d = c->cfg.d_model;
+    if (out == c->xb) c->xb_has_ssq = false;
     hipLaunchKernelGGL((rmsnorm_bf16_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->stream, x, d, (const bf16_t*)gain, c->cfg.rms_eps, d,
                        out, ld);
     HIP_TRY(c, hipGetLastError());
@@ -408,23 +429,47 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
     const int qkv_rows = (g.n_heads + 2 * g.n_kv_heads) * hd;
     int rc;
     if (mfma) {
+        // Decoding blocks (<= 16 rows): the residual products keep K inside the workgroup and hand
+        // gain * x and partial sums of squares to their consumer (no kernel in between).  Prefill
+        // blocks split K over workgroups and fold the partial sums in resid_norm_kernel.
+        // (measured: -10 us per 70B-shape layer; at d_model = 5120 the 320-tile residual products lose
+        // more without their K split than the two small kernels cost, so narrow models keep those)
+        const bool fused = M <= MAX_ROWS && (g_fuse_norm < 0 ? d / 16 >= 448 : g_fuse_norm != 0);
         GemmP p = gemm_base(lw.wqkv, c->xb, d, M, qkv_rows, d);
         fill_qkv(c, p, cache, pos0, 0);
+        take_xb(c, p);
         if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
         if ((rc = launch_attention(c, cache, M, pos0, true))) return rc;
-        int ks = mfma_ksplit(d, qd);
         p = gemm_base(lw.wo, c->ab, qd, M, d, qd);
-        p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->row_cap;
-        if ((rc = gemm_launch<EPI_RESID>(c, true, p, ks))) return rc;
-        if ((rc = launch_resid_norm(c, M, ks, lw.ffn_norm))) return rc;
+        if (fused) {
+            p.Y = c->x; p.ldy = d;
+            fuse_next(c, p, lw.ffn_norm);
+            if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
+            c->xb_has_ssq = true;
+        } else {
+            int ks = mfma_ksplit(d, qd);
+            p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->row_cap;
+            if ((rc = gemm_launch<EPI_RESID>(c, true, p, ks))) return rc;
+            if ((rc = launch_resid_norm(c, M, ks, lw.ffn_norm))) return rc;
+            c->xb_has_ssq = false;
+        }
         p = gemm_base(lw.w_gate_up, c->xb, d, M, 2 * f, d);
         p.Y = c->actb; p.ldy = f; p.y_bf16 = 1;
+        take_xb(c, p);
         if ((rc = gemm_launch<EPI_SWIGLU>(c, true, p))) return rc;
-        ks = mfma_ksplit(d, f);
         p = gemm_base(lw.w_down, c->actb, f, M, d, f);
-        p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->row_cap;
-        if ((rc = gemm_launch<EPI_RESID>(c, true, p, ks))) return rc;
-        if ((rc = launch_resid_norm(c, M, ks, next_gain))) return rc;
+        if (fused) {
+            p.Y = c->x; p.ldy = d;
+            fuse_next(c, p, next_gain);
+            if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
+            c->xb_has_ssq = true;
+        } else {
+            int ks = mfma_ksplit(d, f);
+            p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->row_cap;
+            if ((rc = gemm_launch<EPI_RESID>(c, true, p, ks))) return rc;
+            if ((rc = launch_resid_norm(c, M, ks, next_gain))) return rc;
+            c->xb_has_ssq = false;
+        }
     } else {
         GemmP p = gemm_base(lw.wqkv, c->x, d, M, qkv_rows, d);
         p.gain = lw.attn_norm; p.eps = g.rms_eps;
@@ -459,6 +504,7 @@ static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
     if (mfma) {
         GemmP p = gemm_base(wkv, c->xb, d, M, rows, d);
         fill_qkv(c, p, g.n_layers, pos0, g.n_heads);
+        take_xb(c, p);
         if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
     } else {
         GemmP p = gemm_base(wkv, c->x, d, M, rows, d);
@@ -478,6 +524,8 @@ static int run_head(eesd_ctx* c, const void* norm, const void* head, int x0, int
     if (mfma) {
         GemmP p = gemm_base(head, c->xb + (size_t)x0 * d, d, M, g.vocab, d);
         p.Y = logits; p.ldy = g.vocab;
+        take_xb(c, p);
+        if (p.ssq_in) p.ssq_in += (size_t)x0 * p.ssq_tiles;   // partial sums are [row][tile]
         if ((rc = gemm_launch<EPI_PLAIN>(c, true, p))) return rc;
     } else {
         GemmP p = gemm_base(head, c->x + (size_t)x0 * d, d, M, g.vocab, d);
@@ -661,7 +709,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
-                   c->part_ml, c->rope_cs, c->part, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev};
+                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev};
     for (void* p : dev)
         if (p) hipFree(p);
     if (c->h_table) hipHostFree(c->h_table);
@@ -717,7 +765,8 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->stream = (hipStream_t)hip_stream;
     c->state = ST_CREATED;
     c->kv_pool = nullptr; c->d_table = nullptr; c->h_table = nullptr;
-    c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = c->part = nullptr;
+    c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = c->part = c->ssq = nullptr;
+    c->xb_has_ssq = false;
     c->xb = c->ab = c->actb = nullptr;
     c->blk_tok = c->prompt_dev = c->result_dev = nullptr;
     c->h_result = c->h_prompt = nullptr;
@@ -769,6 +818,8 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if ((rc = dev_alloc(c, &c->part_o, (size_t)MAX_ROWS * g.n_heads * c->max_splits * g.head_dim))) return bail(rc);
     if ((rc = dev_alloc(c, &c->part_ml, (size_t)MAX_ROWS * g.n_heads * c->max_splits * 2))) return bail(rc);
     if ((rc = dev_alloc(c, &c->part, (size_t)MFMA_MAX_KSPLIT * R * d))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->ssq, (size_t)(d / 16) * MAX_ROWS))) return bail(rc);
+    hipMemset(c->ssq, 0, sizeof(float) * (d / 16) * MAX_ROWS);
     if ((rc = dev_alloc(c, &c->xb, R * d))) return bail(rc);
     if ((rc = dev_alloc(c, &c->ab, R * qd))) return bail(rc);
     if ((rc = dev_alloc(c, &c->actb, R * f))) return bail(rc);
