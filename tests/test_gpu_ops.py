@@ -80,6 +80,17 @@ def test_gemm_tile_kernel_chunk_and_workgroup_shapes(kc, nwt, M):
             pk.set_tunable(k, 0)
 
 
+@pytest.mark.parametrize("M", [65, 128])
+def test_gemm_tile_kernel_prefill_chunk_256(M):
+    require_gpu()
+    pk = _pk()
+    try:
+        pk.set_tunable("pf_kc", 256)
+        assert _gemm_case(M, 2048, 1536, torch.bfloat16, pk.GEMM_MFMA, 10) < TOL_BF16
+    finally:
+        pk.set_tunable("pf_kc", 0)
+
+
 @pytest.mark.parametrize("nw", [1, 2, 4, 16])
 def test_gemm_mfma_launch_shapes(nw):
     require_gpu()
@@ -92,7 +103,7 @@ def test_gemm_mfma_launch_shapes(nw):
         pk.set_tunable("mfma_nw", 0)
 
 
-@pytest.mark.parametrize("V", [512, 1000, 32000])
+@pytest.mark.parametrize("V", [512, 1000, 32000, 50257])   # the last one is too long for the LDS-resident row
 def test_softmax_sample_bit_exact_tokens(V):
     require_gpu()
     pk = _pk()
@@ -121,7 +132,7 @@ def test_argmax_ties_lowest_index():
     assert pk.op_softmax_sample(torch.from_numpy(row).cuda(), None, 0.0, 0.0) == 77
 
 
-@pytest.mark.parametrize("V", [512, 32000])
+@pytest.mark.parametrize("V", [512, 32000, 50257])
 @pytest.mark.parametrize("K", [0, 1, 3, 10, 15])
 def test_accept_decision_bit_exact(V, K):
     require_gpu()
