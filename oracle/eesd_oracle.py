@@ -18,13 +18,18 @@ What follows which passage of the paper:
   output keeps the distribution of auto-regressive decoding
 * Beta posterior controller .............. Section 3.3 Eq. 2-4 and Algorithm 2 (Appendix A)
 * v_d, r_d, harmonic mean, speed model ... Section 4.1 "Metrics", Appendix D
+* tree of draft candidates ............... Section 4.3 "Implement Tree Attention" and the
+  caption of its table (a candidate is kept only if it is the target's top-1 token);
+  the tree's shape is this file's reading, stated at OracleEESDTree
 
 Pins (tests/test_oracle_*.py): exact enumeration of the output distribution
 on a tiny vocabulary, greedy speculative == greedy auto-regressive, block
 verification == sequential single-token forwards, rollback == never drafted,
 the transformer against an independent library implementation of the LLaMA
 decoder, closed forms of the Beta posterior, published vectors of the
-counter hash.  Per-seed sampled token streams at temperature 1 are fixed by
+counter hash; for the candidate tree (tests/test_oracle_tree_pins.py): brute force
+over all root paths, equality with greedy auto-regressive decoding, from-scratch
+forwards of every path, caches after rollback.  Per-seed sampled token streams at temperature 1 are fixed by
 nothing but this file: "parity unpinned" by the paper for those.
 
 Storage is float32 only where a value is *input data* (weights) or where the
@@ -467,6 +472,140 @@ class OracleEESD:
             if t + 1 < max_new:
                 logits = self.target_forward([tok], pos)[0]
                 pos += 1
+        return out
+
+
+# ---------------------------------------------------------------------------
+# tree of draft candidates (Section 4.3, "Implement Tree Attention")
+# ---------------------------------------------------------------------------
+
+def top_candidates(logits32: np.ndarray, c: int) -> List[int]:
+    """The c highest entries of an fp32 row, highest first, equal values by lowest index."""
+    order = np.lexsort((np.arange(logits32.shape[0]), -logits32.astype(np.float64)))
+    return [int(t) for t in order[:c]]
+
+
+def tree_walk(children: Sequence[Sequence[int]], top_of: Callable) -> Tuple[int, int, List[int]]:
+    """Greedy acceptance over a tree of candidates.
+
+    children[i] are the candidate tokens at depth i + 1; children[i][0] is the one the draft
+    model went on from, the others are leaves.  top_of(path) is the target model's top-1 token
+    after the committed text followed by `path` (a tuple of tokens).  A candidate is kept only
+    if it IS the target's top-1 token (the caption of the tree-attention table), so the walk
+    follows the target's own greedy continuation for as long as the tree contains it.
+    Returns (a, y, branch): a accepted tokens, the next token y, and which child was taken at
+    each accepted depth."""
+    path: Tuple[int, ...] = ()
+    branch: List[int] = []
+    for kids in children:
+        top = top_of(path)
+        if top not in kids:
+            return len(path), top, branch
+        j = list(kids).index(top)
+        path = path + (top,)
+        branch.append(j)
+        if j != 0:            # a leaf: nothing was drafted below it
+            break
+    return len(path), top_of(path), branch
+
+
+class OracleEESDTree(OracleEESD):
+    """EESD with several candidates per draft step, greedy decoding (temperature 0).
+
+    Reading of Section 4.3 (the paper fixes neither the shape of the tree nor how it is
+    grown): at every draft step the `width` most likely tokens of the draft distribution are
+    candidates; the most likely one is extended by the next draft step, the others are leaves.
+    The target model's output at a node is, by definition, its output on the committed text
+    followed by the path to that node; this oracle evaluates exactly that, one path at a
+    time, with no tree mask."""
+
+    def __init__(self, weights: dict, max_seq: int, width: int, **kw):
+        super().__init__(weights, max_seq, temperature=0.0, **kw)
+        assert width >= 2
+        self.width = width
+        self.children: List[List[int]] = []
+
+    def draft_step_tree(self, force: Optional[Sequence[int]] = None) -> List[int]:
+        i = len(self.children)
+        tok_in = self.pending if i == 0 else self.children[-1][0]
+        logits = self.draft_forward(tok_in, self.kv_len + i)
+        self.q_logits.append(logits)
+        kids = top_candidates(logits.astype(np.float32), self.width)
+        if force is not None:
+            kids = [int(t) for t in force]
+        self.children.append(kids)
+        self.drafts.append(kids[0])
+        return kids
+
+    def node_logits(self) -> dict:
+        """Target logits at every node: {(): row of the pending token, (i, j): child j at depth i}."""
+        K = len(self.children)
+        chain = [self.pending] + [kids[0] for kids in self.children]
+        rows = {}
+        # leaves, deepest first: a leaf at depth i overwrites cache position kv_len + i only,
+        # which shallower nodes never look at
+        full = self.target_forward(chain, self.kv_len)
+        for i in range(K, 0, -1):
+            for j in range(1, self.width):
+                rows[(i, j)] = self.target_forward([self.children[i - 1][j]], self.kv_len + i)[0]
+        full = self.target_forward(chain, self.kv_len)      # the chain's keys and values back in place
+        rows[()] = full[0]
+        for i in range(1, K + 1):
+            rows[(i, 0)] = full[i]
+        return rows
+
+    def verify_accept_tree(self) -> Tuple[int, int, List[int]]:
+        rows = self.node_logits()
+        self.tree_logits = rows
+
+        def top_of(path):
+            if not path:
+                return argmax_lowest(rows[()].astype(np.float32))
+            i = len(path)
+            j = self.children[i - 1].index(path[-1])
+            return argmax_lowest(rows[(i, j)].astype(np.float32))
+
+        self.last_tree = tree_walk(self.children, top_of)
+        return self.last_tree
+
+    def rollback_tree(self, a: int, y: int, branch: Sequence[int]) -> List[int]:
+        """Commits the accepted path; returns its tokens.  The caches must hold the keys and
+        values of the committed tokens: an accepted leaf is put where the chain token was."""
+        K = len(self.children)
+        toks = [self.children[i][branch[i]] for i in range(a)]
+        if a and branch[a - 1] != 0:
+            self.target_forward([toks[-1]], self.kv_len + a)
+        self.kv_len += a + 1
+        self.pending = int(y)
+        self.ts.update(a, K)
+        self.stats.rounds += 1
+        self.stats.drafted += K
+        self.stats.accepted += a
+        self.children, self.drafts, self.q_rows, self.q_logits = [], [], [], []
+        self.rnd += 1
+        return toks
+
+    def generate_tree(self, prompt: Sequence[int], max_new: int, fixed_k: Optional[int] = None,
+                      k_schedule: Optional[Sequence[int]] = None, trace: Optional[list] = None) -> List[int]:
+        out = [self.prefill(prompt)]
+        r = 0
+        while len(out) < max_new:
+            k_max = min(self.k_cap, max_new - len(out))
+            if k_schedule is not None:
+                K = min(int(k_schedule[r]), k_max)
+            elif fixed_k is not None:
+                K = min(fixed_k, k_max)
+            else:
+                K = self.ts.draw_k(self.rnd, k_max)
+            for _ in range(K):
+                self.draft_step_tree()
+            a, y, branch = self.verify_accept_tree()
+            if trace is not None:
+                trace.append(dict(K=K, a=a, y=y, branch=list(branch), children=[list(k) for k in self.children], base=self.kv_len))
+            out.extend(self.rollback_tree(a, y, branch) + [y])
+            r += 1
+        out = out[:max_new]
+        self.stats.generated = len(out)
         return out
 
 
