@@ -125,6 +125,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="70b", choices=sorted(WORKLOADS))
     ap.add_argument("--temperature", type=float, default=1.0)
+    ap.add_argument("--tree-width", type=int, default=0,
+                    help="2..4: candidate-tree verification (greedy decoding; temperature is set to 0 and K is capped so that 1 + K * width <= 16)")
+    ap.add_argument("--draft-correlation", type=float, default=None,
+                    help="gamma of synth_inputs.make_weights(correlated_draft=gamma): a synthetic draft model that agrees with the "
+                         "target often (independent random weights almost never do under greedy decoding)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--latency-sweep", action="store_true",
                     help="also report draft-step and verify-pass latency versus K over a pre-filled cache (outside the timed region)")
@@ -146,16 +151,19 @@ def main():
     pk.lib()  # fails loudly if libeesd.so is not built
     shape_key, wseed, n_prompt, max_new, k_cap = WORKLOADS[args.workload]
     shape = getattr(si, shape_key)
+    if args.tree_width >= 2:
+        args.temperature = 0.0
+        k_cap = min(k_cap, 15 // args.tree_width)
     t0 = time.perf_counter()
-    w = si.make_weights(shape, seed=wseed, device="cuda")
+    w = si.make_weights(shape, seed=wseed, device="cuda", correlated_draft=args.draft_correlation)
     torch.cuda.synchronize()
     t_weights = time.perf_counter() - t0
-    max_seq = n_prompt + max_new + k_cap + 2
+    max_seq = n_prompt + max_new + k_cap * max(1, args.tree_width) + 2
     sweep_tokens = 2048 if args.workload == "70b" else n_prompt       # cache length of the latency sweep
     if args.latency_sweep:
         max_seq = max(max_seq, sweep_tokens + k_cap + 2)
     max_seq = (max_seq + 63) // 64 * 64
-    ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64)
+    ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64, tree_width=args.tree_width)
     prompt = si.make_prompt(n_prompt, shape["vocab"], 0)
 
     if args.calibration_copy:
@@ -206,7 +214,9 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"full EESD generation, {shape['name']} (L={L}, N={N}), random weights seed {wseed}, "
                                f"prompt {n_prompt} uniform ids, {max_new} new tokens, Beta-TS K cap {k_cap}, "
-                               f"temperature {args.temperature:g}, batch 1",
+                               f"temperature {args.temperature:g}, batch 1"
+                               + (f", candidate tree of width {args.tree_width}" if args.tree_width >= 2 else "")
+                               + (f", draft correlated with the target (gamma {args.draft_correlation:g})" if args.draft_correlation is not None else ""),
                    "prefill": "included in every step (128-row blocks, tiled MFMA product)" if bf16 else "included in every step (16-row blocks)"},
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<SWIGLU> (gate/up product of the draft and verify passes)" if bf16
                      else "gemm_valu_kernel<SWIGLU>",

@@ -75,7 +75,11 @@ typedef struct eesd_config {
     int32_t ts_update;       /* reading of Eq. 3-4: 0: r = a, n = min(a+1, K) (drafts the target judged);
                                 1: |Q_v| = a+1 taken literally, r = a, n = min(a+2, K) */
     int32_t gemm_path;       /* EESD_GEMM_*: AUTO picks per pass; the others force one kernel family */
-    int32_t reserved;
+    int32_t tree_width;      /* 0 or 1: one draft token per step (Algorithm 1).  2..4: candidate tree (Section 4.3,
+                                tree-attention table): every draft step proposes its tree_width most likely tokens,
+                                the first is drafted on from, the others are leaves; one verify pass judges all
+                                1 + K * tree_width rows under a tree mask and keeps only candidates that are the
+                                target's top-1 token.  Needs temperature == 0 and 1 + k_cap * tree_width <= 16 */
 } eesd_config;
 
 /* One decoder layer.  Every matrix is row-major [out][in] in the configured dtype. */
@@ -144,6 +148,10 @@ int eesd_draft_step(eesd_ctx* ctx, int32_t* tok_or_null);
  * the last rollback, K = 0 allowed: a plain auto-regressive step), against the paged
  * KV cache.  Leaves K+1 rows of target logits on the device.  Does not synchronise. */
 int eesd_verify(eesd_ctx* ctx);
+/* Tree mode (tree_width = w >= 2): the block has 1 + K*w rows - row 0 the pending token, rows
+ * 1 + (i-1)*w + j the j-th candidate of depth i (j = 0: the one drafted on from).  A row is
+ * written to cache slot base + row, rotated for position base + depth, and attends to the cache,
+ * row 0, the j = 0 rows of the depths above it, and itself. */
 
 /* Accept / resample.  Greedy: drafts are kept while equal to the target's top-1; the
  * next token is the top-1 after them.  Sampling: draft i is accepted iff
@@ -153,6 +161,14 @@ int eesd_verify(eesd_ctx* ctx);
  * resample/bonus draw); NULL uses the context's counter-based uniforms.
  * Synchronises; returns a = *n_accepted and y = *next_token. */
 int eesd_accept(eesd_ctx* ctx, const double* uniforms_or_null, int32_t* n_accepted, int32_t* next_token);
+
+/* The tokens the last eesd_accept kept, in order (without the next token): the first a drafts,
+ * or, in tree mode (Section 4.3), the tokens of the accepted root path, whose last node may be
+ * a leaf candidate.  In tree mode eesd_accept has already moved the accepted nodes' keys and
+ * values to their final positions in every cache, uniforms are ignored, and eesd_rollback takes
+ * at most the a it returned.  toks: HOST array of at least `cap` entries; *n receives a.
+ * Valid between eesd_accept and the next eesd_accept. */
+int eesd_accepted_tokens(eesd_ctx* ctx, int32_t* toks, int32_t cap, int32_t* n);
 
 /* Keeps the accepted prefix: the valid length of every layer's KV cache (and of the
  * early-exit layer's) becomes base + n_accepted + 1, whole pages past it return to the
@@ -199,7 +215,8 @@ enum {
     EESD_READ_KV_V = 4,
     EESD_READ_TOKENS = 5,        /* the block [pending, d_1..d_K] as int32 */
     EESD_READ_KV_LEN = 6,        /* one int32 */
-    EESD_READ_PAGE_TABLE = 7     /* ceil(max_seq / kv_page) int32 (-1 = unmapped) */
+    EESD_READ_PAGE_TABLE = 7,    /* ceil(max_seq / kv_page) int32 (-1 = unmapped) */
+    EESD_READ_TREE_TOKENS = 8    /* tree mode: the tokens of the block's 1 + K * tree_width rows as int32 */
 };
 /* Copies internal state to HOST memory as fp32 / int32.  Synchronises.  n_tokens limits KV reads. */
 int eesd_debug_read(eesd_ctx* ctx, int what, int index, int32_t n_tokens, void* host_dst, size_t bytes);

@@ -15,7 +15,7 @@ import numpy as np
 DTYPE_F32, DTYPE_BF16 = 0, 1
 TS_BETA, TS_FIXED, TS_SCHEDULE = 0, 1, 2
 GEMM_AUTO, GEMM_VALU, GEMM_MFMA = 0, 1, 2
-READ_DRAFT_LOGITS, READ_DRAFT_PROBS, READ_VERIFY_LOGITS, READ_KV_K, READ_KV_V, READ_TOKENS, READ_KV_LEN, READ_PAGE_TABLE = range(8)
+READ_DRAFT_LOGITS, READ_DRAFT_PROBS, READ_VERIFY_LOGITS, READ_KV_K, READ_KV_V, READ_TOKENS, READ_KV_LEN, READ_PAGE_TABLE, READ_TREE_TOKENS = range(9)
 
 _STATUS = {0: "EESD_OK", -1: "EESD_EINVAL", -2: "EESD_ENOMEM", -3: "EESD_ESTATE", -4: "EESD_ERANGE", -5: "EESD_EDEVICE"}
 
@@ -32,7 +32,7 @@ class _Config(C.Structure):
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_seq", C.c_int32),
                 ("kv_page", C.c_int32), ("k_cap", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
                 ("ts_alpha0", C.c_double), ("ts_beta0", C.c_double), ("ts_mode", C.c_int32), ("ts_update", C.c_int32),
-                ("gemm_path", C.c_int32), ("reserved", C.c_int32)]
+                ("gemm_path", C.c_int32), ("tree_width", C.c_int32)]
 
 
 class _Layer(C.Structure):
@@ -72,7 +72,7 @@ def lib_path() -> str:
 
 
 _LIB = None
-EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_rollback",
+EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_accepted_tokens", "eesd_rollback",
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
            "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
@@ -95,6 +95,7 @@ def lib() -> C.CDLL:
     L.eesd_draft_step.argtypes = [VP, P(I32)]
     L.eesd_verify.argtypes = [VP]
     L.eesd_accept.argtypes = [VP, P(C.c_double), P(I32), P(I32)]
+    L.eesd_accepted_tokens.argtypes = [VP, P(I32), I32, P(I32)]
     L.eesd_rollback.argtypes = [VP, I32]
     L.eesd_generate.argtypes = [VP, P(I32), I32, I32, P(I32), P(I32), P(_Stats)]
     L.eesd_get_stats.argtypes = [VP, P(_Stats)]
@@ -163,14 +164,14 @@ class EESD:
 
     def __init__(self, weights: dict, max_seq: int, temperature: float, seed: int = 0, k_cap: int = 10,
                  kv_page: int = 16, alpha0: float = 1.0, beta0: float = 1.0, ts_mode: int = TS_BETA,
-                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0):
+                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0, tree_width: int = 0):
         sh = weights["shape"]
         self._keep = weights
         self.shape = sh
         self.vocab = sh["vocab"]
         cfg = _Config(sh["n_layers"], sh["n_draft_layers"], sh["d_model"], sh["n_heads"], sh["n_kv_heads"], sh["head_dim"],
                       sh["d_ff"], sh["vocab"], sh["rms_eps"], sh["rope_base"], DTYPE_BF16 if sh["dtype"] == "bf16" else DTYPE_F32,
-                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, 0)
+                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, tree_width)
 
         def lw(d):
             return _Layer(*[d[k].data_ptr() for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
@@ -183,6 +184,7 @@ class EESD:
             self._h = None
             raise EesdError(rc, "eesd_create")
         self.k_cap = k_cap
+        self.tree_width = tree_width
 
     def close(self):
         if getattr(self, "_h", None):
@@ -222,6 +224,12 @@ class EESD:
             u = np.ascontiguousarray(np.asarray(uniforms, dtype=np.float64))
             self._ck(lib().eesd_accept(self._h, _ptr(u, C.c_double), C.byref(a), C.byref(y)))
         return a.value, y.value
+
+    def accepted_tokens(self) -> List[int]:
+        toks = np.zeros(16, np.int32)
+        n = C.c_int32()
+        self._ck(lib().eesd_accepted_tokens(self._h, _ptr(toks, C.c_int32), 16, C.byref(n)))
+        return toks[: n.value].tolist()
 
     def rollback(self, n_accepted: int) -> None:
         self._ck(lib().eesd_rollback(self._h, int(n_accepted)))
@@ -292,6 +300,9 @@ class EESD:
 
     def block_tokens(self, n: int) -> List[int]:
         return self._read(READ_TOKENS, 0, 0, np.empty(n, np.int32)).tolist()
+
+    def tree_tokens(self, n: int) -> List[int]:
+        return self._read(READ_TREE_TOKENS, 0, 0, np.empty(n, np.int32)).tolist()
 
     def page_table(self, n_pages: int) -> List[int]:
         return self._read(READ_PAGE_TABLE, 0, 0, np.empty(n_pages, np.int32)).tolist()

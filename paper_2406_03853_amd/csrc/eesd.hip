@@ -19,7 +19,11 @@
 #include "gemm.hiph"
 #include "sampling.hiph"
 
-#define MAX_ROWS 16    // rows of a decoding pass: 1 (draft) .. k_cap + 1 (verify)
+#define MAX_ROWS 16    // rows of a decoding pass: 1 (draft) .. k_cap + 1 (verify; 1 + k_cap * width in tree mode)
+// pinned result words: [0] a, [1] y, [2] draft token, [3] token hooks, [4..4+MAX_ROWS) accepted rows, [24..24+MAX_ROWS+1) block tokens
+#define H_RESULT_INTS 48
+#define H_ROWS_AT 4
+#define H_TOKS_AT 24
 #define PREFILL_ROWS 128  // rows of a prefill block when the tiled MFMA product applies
 
 // ---------------------------------------------------------------------------------------------
@@ -110,7 +114,13 @@ struct eesd_ctx {
     bool xb_has_ssq;       // c->xb holds gain * x (bf16) and c->ssq the partial sums of squares of x, instead of RMSNorm(x)
     bf16_t *xb, *ab, *actb;
     int32_t *blk_tok, *prompt_dev, *result_dev;
+    int32_t *tree_blk;     // tree mode: tokens of the verify block's rows (pending token, then `width` children per depth)
     int32_t *h_result, *h_prompt;  // pinned
+    // candidate tree
+    bool tree_active;               // the rows being processed are tree nodes (verify in tree mode)
+    unsigned short tree_mask[16];   // visible block rows per row
+    unsigned char tree_depth[16];   // rotary offset per row
+    std::vector<int32_t> last_tokens;   // tokens the last accept kept (drafts or tree nodes), without the next token
     int max_splits;
     int row_cap;           // rows the activation buffers hold (16, or PREFILL_ROWS)
     hipEvent_t ev[4];
@@ -379,6 +389,10 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
     a.out = out_bf16 ? (void*)c->ab : (void*)c->attn;
     a.out_bf16 = out_bf16;
     a.part_o = c->part_o; a.part_ml = c->part_ml;
+    if (c->tree_active) {
+        a.tree = 1;
+        memcpy(a.tree_mask, c->tree_mask, sizeof a.tree_mask);
+    }
     if (kb) {
         dim3 grid(n_splits * g.n_kv_heads, (qtiles + 7) / 8);
         const int nwq = std::min(qtiles, 8);
@@ -413,6 +427,10 @@ static void fill_qkv(eesd_ctx* c, GemmP& p, int cache, int pos0, int head0) {
     p.head0 = head0; p.pos0 = pos0; p.rope_cs = c->rope_cs;
     p.kv = kv_view(c, cache);
     p.kv_bf16 = is_bf16(c);
+    if (c->tree_active) {
+        p.tree = 1;
+        memcpy(p.rope_off, c->tree_depth, sizeof p.rope_off);
+    }
 }
 
 static int launch_resid_norm(eesd_ctx* c, int M, int ksplit, const void* gain) {
@@ -712,7 +730,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
-                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev};
+                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk};
     for (void* p : dev)
         if (p) hipFree(p);
     if (c->h_table) hipHostFree(c->h_table);
@@ -735,6 +753,8 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if (g.dtype != EESD_DTYPE_F32 && g.dtype != EESD_DTYPE_BF16) return EESD_EINVAL;
     if (!(g.temperature >= 0.0f) || !(g.ts_alpha0 > 0.0) || !(g.ts_beta0 > 0.0)) return EESD_EINVAL;
     if (g.ts_mode < 0 || g.ts_mode > 2 || g.ts_update < 0 || g.ts_update > 1 || g.gemm_path < 0 || g.gemm_path > 2) return EESD_EINVAL;
+    if (g.tree_width < 0 || g.tree_width > TREE_MAX_WIDTH) return EESD_EINVAL;
+    if (g.tree_width >= 2 && (g.temperature != 0.0f || 1 + g.k_cap * g.tree_width > MAX_ROWS)) return EESD_EINVAL;
     const int vec = g.dtype == EESD_DTYPE_BF16 ? 8 : 4;
     const int qd = g.n_heads * g.head_dim;
     if (g.d_model % vec || g.d_ff % vec || qd % vec || g.vocab % 4 || g.d_ff % 2) return EESD_EINVAL;
@@ -771,7 +791,8 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = c->part = c->ssq = nullptr;
     c->xb_has_ssq = false;
     c->xb = c->ab = c->actb = nullptr;
-    c->blk_tok = c->prompt_dev = c->result_dev = nullptr;
+    c->blk_tok = c->prompt_dev = c->result_dev = c->tree_blk = nullptr;
+    c->tree_active = false;
     c->h_result = c->h_prompt = nullptr;
     for (auto& e : c->ev) e = nullptr;
     c->alpha = g.ts_alpha0; c->beta = g.ts_beta0;
@@ -795,7 +816,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if (hipMalloc(&c->kv_pool, pool_bytes) != hipSuccess) return bail(EESD_ENOMEM);
     if ((rc = dev_alloc(c, &c->d_table, c->n_pages))) return bail(rc);
     if (hipHostMalloc((void**)&c->h_table, sizeof(int32_t) * c->n_pages, hipHostMallocDefault) != hipSuccess) return bail(EESD_ENOMEM);
-    if (hipHostMalloc((void**)&c->h_result, sizeof(int32_t) * 4, hipHostMallocDefault) != hipSuccess) return bail(EESD_ENOMEM);
+    if (hipHostMalloc((void**)&c->h_result, sizeof(int32_t) * H_RESULT_INTS, hipHostMallocDefault) != hipSuccess) return bail(EESD_ENOMEM);
     if (hipHostMalloc((void**)&c->h_prompt, sizeof(int32_t) * g.max_seq, hipHostMallocDefault) != hipSuccess) return bail(EESD_ENOMEM);
     // physical pages are handed out in reverse order, so logical != physical from the start
     for (int p = 0; p < c->n_pages; ++p) { c->free_pages.push_back(p); c->h_table[p] = -1; }
@@ -828,7 +849,8 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if ((rc = dev_alloc(c, &c->actb, R * f))) return bail(rc);
     if ((rc = dev_alloc(c, &c->blk_tok, (size_t)MAX_ROWS + 1))) return bail(rc);
     if ((rc = dev_alloc(c, &c->prompt_dev, (size_t)g.max_seq))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->result_dev, (size_t)4))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->result_dev, (size_t)2 + MAX_ROWS))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->tree_blk, (size_t)MAX_ROWS + 1))) return bail(rc);
     // rows of the bf16 activation buffers past M are read (and ignored) by the MFMA product
     hipMemset(c->xb, 0, sizeof(bf16_t) * R * d);
     hipMemset(c->ab, 0, sizeof(bf16_t) * R * qd);
@@ -877,6 +899,10 @@ static hipError_t smp_allow(F fn, int V) { return allow_lds((const void*)fn, smp
 static float inv_temperature(const eesd_ctx* c) { return c->cfg.temperature > 0.f ? 1.0f / c->cfg.temperature : 1.0f; }
 static int greedy(const eesd_ctx* c) { return c->cfg.temperature == 0.f; }
 
+static int tree_width(const eesd_ctx* c) { return c->cfg.tree_width >= 2 ? c->cfg.tree_width : 1; }
+// most rows a verify block can have
+static int rows_cap(const eesd_ctx* c) { return 1 + c->cfg.k_cap * tree_width(c); }
+
 static void reset_sequence(eesd_ctx* c) {
     release_pages(c, 0);
     c->kv_len = 0; c->n_drafted = 0; c->round = 0; c->sched_round = 0;
@@ -889,7 +915,7 @@ extern "C" int eesd_prefill(eesd_ctx* c, const int32_t* prompt, int32_t n, int32
     if (!c) return EESD_EINVAL;
     if (!prompt || !first_token || n < 1) return fail(c, EESD_EINVAL, "prefill: null pointer or empty prompt");
     const eesd_config& g = c->cfg;
-    if (n + g.k_cap + 1 > g.max_seq) return fail(c, EESD_ERANGE, "prefill: prompt of %d tokens + k_cap + 1 exceeds max_seq %d", n, g.max_seq);
+    if (n + rows_cap(c) > g.max_seq) return fail(c, EESD_ERANGE, "prefill: prompt of %d tokens + a verify block of %d rows exceeds max_seq %d", n, rows_cap(c), g.max_seq);
     for (int i = 0; i < n; ++i)
         if (prompt[i] < 0 || prompt[i] >= g.vocab) return fail(c, EESD_EINVAL, "prefill: token %d at %d outside [0,%d)", prompt[i], i, g.vocab);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -933,7 +959,8 @@ extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
     const int i = c->n_drafted;
     if (i >= g.k_cap) return fail(c, EESD_ERANGE, "draft_step: k_cap = %d drafts already made", g.k_cap);
     const int pos = c->kv_len + i;
-    if (pos + 2 > g.max_seq) return fail(c, EESD_ERANGE, "draft_step: position %d does not leave room for verification (max_seq %d)", pos, g.max_seq);
+    if (c->kv_len + 1 + (i + 1) * tree_width(c) > g.max_seq)
+        return fail(c, EESD_ERANGE, "draft_step: position %d does not leave room for verification (max_seq %d)", pos, g.max_seq);
     int rc = ensure_pages(c, pos + 1);
     if (rc) return rc;
     const bool mfma = pick_mfma(c, 1);
@@ -947,13 +974,26 @@ extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
     if ((rc = run_layer(c, c->w.ee_layer, g.n_layers, 1, pos, mfma, c->w.ee_norm))) return rc;
     float* ql = c->q_logits + (size_t)i * g.vocab;
     if ((rc = run_head(c, c->w.ee_norm, c->w.ee_head, 0, 1, ql, mfma))) return rc;
-    int forced = -1;
-    if (c->forced_pos < c->forced.size()) forced = c->forced[c->forced_pos++];
-    double u = uniform53(g.seed, STREAM_DRAFT, c->round, i, 0);
-    HIP_TRY(c, smp_allow(softmax_sample_kernel, g.vocab));
-    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, ql,
-                       c->q_rows + (size_t)i * g.vocab, g.vocab, inv_temperature(c), greedy(c), u, forced, c->blk_tok + i + 1,
-                       smp_use_lds(g.vocab));
+    const int width = tree_width(c);
+    if (width > 1) {
+        // the `width` most likely tokens are this depth's candidates; the first is drafted on from
+        TreeForced tf;
+        for (int j = 0; j < TREE_MAX_WIDTH; ++j) tf.tok[j] = -1;
+        if (c->forced_pos + width <= c->forced.size()) {
+            for (int j = 0; j < width; ++j) tf.tok[j] = c->forced[c->forced_pos + j];
+            c->forced_pos += width;
+        }
+        hipLaunchKernelGGL(top_candidates_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, ql, g.vocab, width, tf,
+                           c->tree_blk + 1 + i * width, c->blk_tok + i + 1);
+    } else {
+        int forced = -1;
+        if (c->forced_pos < c->forced.size()) forced = c->forced[c->forced_pos++];
+        double u = uniform53(g.seed, STREAM_DRAFT, c->round, i, 0);
+        HIP_TRY(c, smp_allow(softmax_sample_kernel, g.vocab));
+        hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, ql,
+                           c->q_rows + (size_t)i * g.vocab, g.vocab, inv_temperature(c), greedy(c), u, forced, c->blk_tok + i + 1,
+                           smp_use_lds(g.vocab));
+    }
     HIP_TRY(c, hipGetLastError());
     c->n_drafted = i + 1;
     if (tok_or_null) {
@@ -968,14 +1008,64 @@ extern "C" int eesd_verify(eesd_ctx* c) {
     if (!c) return EESD_EINVAL;
     if (c->state != ST_READY) return fail(c, EESD_ESTATE, "verify: state is not ready");
     const eesd_config& g = c->cfg;
-    const int M = c->n_drafted + 1;
+    const int width = tree_width(c);
+    const int M = 1 + c->n_drafted * width;
     if (c->kv_len + M > g.max_seq) return fail(c, EESD_ERANGE, "verify: %d rows at %d exceed max_seq %d", M, c->kv_len, g.max_seq);
     int rc = ensure_pages(c, c->kv_len + M);
     if (rc) return rc;
     const bool mfma = pick_mfma(c, M);
-    if ((rc = run_target_rows(c, c->blk_tok, M, c->kv_len, mfma))) return rc;
+    const int32_t* rows_tok = c->blk_tok;
+    if (width > 1) {
+        // rows: the pending token, then `width` children per depth; a node sees the pending token,
+        // the first children of the depths above it, and itself
+        HIP_TRY(c, hipMemcpyAsync(c->tree_blk, c->blk_tok, sizeof(int32_t), hipMemcpyDeviceToDevice, c->stream));
+        memset(c->tree_mask, 0, sizeof c->tree_mask);
+        memset(c->tree_depth, 0, sizeof c->tree_depth);
+        c->tree_mask[0] = 1;
+        unsigned chain = 1;   // row 0 and the first children so far
+        for (int i = 0; i < c->n_drafted; ++i) {
+            for (int j = 0; j < width; ++j) {
+                const int r = 1 + i * width + j;
+                c->tree_mask[r] = (unsigned short)(chain | (1u << r));
+                c->tree_depth[r] = (unsigned char)(i + 1);
+            }
+            chain |= 1u << (1 + i * width);
+        }
+        c->tree_active = true;
+        rows_tok = c->tree_blk;
+    }
+    rc = run_target_rows(c, rows_tok, M, c->kv_len, mfma);
+    c->tree_active = false;
+    if (rc) return rc;
     if ((rc = run_head(c, c->w.final_norm, c->w.lm_head, 0, M, c->logits, mfma))) return rc;
     c->state = ST_VERIFIED;
+    return EESD_OK;
+}
+
+// Tree mode (greedy): the walk over the candidates, then the accepted nodes' keys and values are
+// moved to the positions they now hold - both queued before the one synchronisation.
+static int accept_tree(eesd_ctx* c, int32_t* n_accepted, int32_t* next_token) {
+    const eesd_config& g = c->cfg;
+    const int K = c->n_drafted, width = tree_width(c), M = 1 + K * width;
+    hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, c->logits, c->tree_blk, K, width, g.vocab, c->result_dev,
+                       c->blk_tok);
+    HIP_TRY(c, hipGetLastError());
+    const int per = c->n_caches * g.n_kv_heads * g.head_dim;
+    KVView v = kv_view(c, 0);
+    if (is_bf16(c)) hipLaunchKernelGGL((kv_compact_kernel<bf16_t>), dim3((per + 255) / 256), dim3(256), 0, c->stream, v, c->n_caches, c->kv_len, c->result_dev);
+    else hipLaunchKernelGGL((kv_compact_kernel<float>), dim3((per + 255) / 256), dim3(256), 0, c->stream, v, c->n_caches, c->kv_len, c->result_dev);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipMemcpyAsync(c->h_result, c->result_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    if (K) HIP_TRY(c, hipMemcpyAsync(c->h_result + H_ROWS_AT, c->result_dev + 2, K * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->h_result + H_TOKS_AT, c->tree_blk, M * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->last_a = c->h_result[0];
+    c->last_y = c->h_result[1];
+    c->last_tokens.clear();
+    for (int i = 0; i < c->last_a; ++i) c->last_tokens.push_back(c->h_result[H_TOKS_AT + c->h_result[H_ROWS_AT + i]]);
+    c->state = ST_ACCEPTED;
+    *n_accepted = c->last_a;
+    *next_token = c->last_y;
     return EESD_OK;
 }
 
@@ -985,6 +1075,7 @@ extern "C" int eesd_accept(eesd_ctx* c, const double* uniforms_or_null, int32_t*
     if (c->state != ST_VERIFIED) return fail(c, EESD_ESTATE, "accept: nothing verified");
     const eesd_config& g = c->cfg;
     const int K = c->n_drafted;
+    if (tree_width(c) > 1) return accept_tree(c, n_accepted, next_token);
     AcceptU uu;
     memset(&uu, 0, sizeof uu);
     for (int i = 0; i < K; ++i) uu.u[i] = uniforms_or_null ? uniforms_or_null[i] : uniform53(g.seed, STREAM_ACCEPT, c->round, i, 0);
@@ -996,12 +1087,24 @@ extern "C" int eesd_accept(eesd_ctx* c, const double* uniforms_or_null, int32_t*
                        c->blk_tok + 1, K, g.vocab, inv_temperature(c), greedy(c), 1, uu, c->result_dev, c->blk_tok, smp_use_lds(g.vocab));
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipMemcpyAsync(c->h_result, c->result_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    if (K) HIP_TRY(c, hipMemcpyAsync(c->h_result + H_TOKS_AT, c->blk_tok + 1, K * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->last_a = c->h_result[0];
     c->last_y = c->h_result[1];
+    c->last_tokens.assign(c->h_result + H_TOKS_AT, c->h_result + H_TOKS_AT + c->last_a);
     c->state = ST_ACCEPTED;
     *n_accepted = c->last_a;
     *next_token = c->last_y;
+    return EESD_OK;
+}
+
+extern "C" int eesd_accepted_tokens(eesd_ctx* c, int32_t* toks, int32_t cap, int32_t* n) {
+    if (!c) return EESD_EINVAL;
+    if (!toks || !n) return fail(c, EESD_EINVAL, "accepted_tokens: null pointer");
+    if (c->state != ST_ACCEPTED) return fail(c, EESD_ESTATE, "accepted_tokens: nothing accepted");
+    if ((size_t)cap < c->last_tokens.size()) return fail(c, EESD_ERANGE, "accepted_tokens: room for %d of %d tokens", cap, (int)c->last_tokens.size());
+    for (size_t i = 0; i < c->last_tokens.size(); ++i) toks[i] = c->last_tokens[i];
+    *n = (int32_t)c->last_tokens.size();
     return EESD_OK;
 }
 
@@ -1010,6 +1113,8 @@ extern "C" int eesd_rollback(eesd_ctx* c, int32_t n_accepted) {
     if (c->state != ST_ACCEPTED) return fail(c, EESD_ESTATE, "rollback: nothing accepted");
     const int K = c->n_drafted;
     if (n_accepted < 0 || n_accepted > K) return fail(c, EESD_ERANGE, "rollback: n_accepted %d outside [0,%d]", n_accepted, K);
+    if (tree_width(c) > 1 && n_accepted > c->last_a)
+        return fail(c, EESD_ERANGE, "rollback: tree mode keeps at most the %d accepted nodes", c->last_a);
     // the stream is idle here: eesd_accept synchronised it
     c->kv_len += n_accepted + 1;
     release_pages(c, c->kv_len);
@@ -1051,8 +1156,8 @@ extern "C" int eesd_generate(eesd_ctx* c, const int32_t* prompt, int32_t n_promp
     if (!c) return EESD_EINVAL;
     if (!prompt || !out || !n_out || max_new < 1) return fail(c, EESD_EINVAL, "generate: null pointer or max_new < 1");
     const eesd_config& g = c->cfg;
-    if (n_prompt + max_new + g.k_cap + 1 > g.max_seq)
-        return fail(c, EESD_ERANGE, "generate: %d prompt + %d new + k_cap + 1 exceeds max_seq %d", n_prompt, max_new, g.max_seq);
+    if (n_prompt + max_new + rows_cap(c) > g.max_seq)
+        return fail(c, EESD_ERANGE, "generate: %d prompt + %d new + a verify block of %d rows exceeds max_seq %d", n_prompt, max_new, rows_cap(c), g.max_seq);
     auto t_begin = std::chrono::steady_clock::now();
     int32_t tok;
     int rc = eesd_prefill(c, prompt, n_prompt, &tok);
@@ -1061,7 +1166,6 @@ extern "C" int eesd_generate(eesd_ctx* c, const int32_t* prompt, int32_t n_promp
     int n = 0;
     out[n++] = tok;
     double ms_d = 0, ms_v = 0, ms_a = 0;
-    std::vector<int32_t> drafts(g.k_cap + 1);
     while (n < max_new) {
         const int K = draw_k(c, std::min((int)g.k_cap, max_new - n));
         HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
@@ -1070,8 +1174,7 @@ extern "C" int eesd_generate(eesd_ctx* c, const int32_t* prompt, int32_t n_promp
         HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
         if ((rc = eesd_verify(c))) return rc;
         HIP_TRY(c, hipEventRecord(c->ev[2], c->stream));
-        // drafts come back together with the decision: one synchronisation per round
-        HIP_TRY(c, hipMemcpyAsync(c->h_prompt, c->blk_tok + 1, sizeof(int32_t) * K, hipMemcpyDeviceToHost, c->stream));
+        // the block's tokens come back together with the decision: one synchronisation per round
         int32_t a, y;
         if ((rc = eesd_accept(c, nullptr, &a, &y))) return rc;
         HIP_TRY(c, hipEventRecord(c->ev[3], c->stream));
@@ -1079,7 +1182,7 @@ extern "C" int eesd_generate(eesd_ctx* c, const int32_t* prompt, int32_t n_promp
         ms_d += ms_between(c->ev[0], c->ev[1]);
         ms_v += ms_between(c->ev[1], c->ev[2]);
         ms_a += ms_between(c->ev[2], c->ev[3]);
-        for (int i = 0; i < a && n < max_new; ++i) out[n++] = c->h_prompt[i];
+        for (int i = 0; i < a && n < max_new; ++i) out[n++] = c->last_tokens[i];
         if (n < max_new) out[n++] = y;
         if ((rc = eesd_rollback(c, a))) return rc;
     }
@@ -1149,7 +1252,7 @@ __global__ void kv_pattern_kernel(KVView kv, int n_tokens, unsigned salt) {
 extern "C" int eesd_debug_fill_cache(eesd_ctx* c, int32_t n_tokens, int32_t pending_tok) {
     if (!c) return EESD_EINVAL;
     const eesd_config& g = c->cfg;
-    if (n_tokens < 1 || n_tokens + g.k_cap + 1 > g.max_seq) return fail(c, EESD_ERANGE, "fill_cache: %d tokens do not fit", n_tokens);
+    if (n_tokens < 1 || n_tokens + rows_cap(c) > g.max_seq) return fail(c, EESD_ERANGE, "fill_cache: %d tokens do not fit", n_tokens);
     if (pending_tok < 0 || pending_tok >= g.vocab) return fail(c, EESD_EINVAL, "fill_cache: token out of range");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     reset_sequence(c);
@@ -1213,6 +1316,12 @@ extern "C" int eesd_debug_read(eesd_ctx* c, int what, int index, int32_t n_token
             size_t need = sizeof(int32_t) * (c->n_drafted + 1);
             if (bytes < need) return fail(c, EESD_ERANGE, "debug_read: destination too small");
             HIP_TRY(c, hipMemcpy(host_dst, c->blk_tok, need, hipMemcpyDeviceToHost));
+            return EESD_OK;
+        }
+        case EESD_READ_TREE_TOKENS: {
+            size_t need = sizeof(int32_t) * (1 + c->n_drafted * tree_width(c));
+            if (tree_width(c) < 2 || bytes < need) return fail(c, EESD_ERANGE, "debug_read: not in tree mode or destination too small");
+            HIP_TRY(c, hipMemcpy(host_dst, c->tree_blk, need, hipMemcpyDeviceToHost));
             return EESD_OK;
         }
         case EESD_READ_KV_LEN: {

@@ -28,8 +28,12 @@ def make_pair(shape, wseed, max_seq, temperature, k_cap=5, jitter=0.1, gamma=Non
     gen_device="cuda" draws big models on the GPU and copies them to the host for the oracle."""
     import paper_2406_03853_amd as pk
     w = si.make_weights(shape, seed=wseed, norm_gain_jitter=jitter, correlated_draft=gamma, device=gen_device)
-    o = orc.OracleEESD(si.weights_to_numpy(w), max_seq, temperature, seed=kw.get("seed", 0), k_cap=k_cap,
-                       ts_update="literal" if kw.get("ts_update", 0) else "prose")
+    if kw.get("tree_width", 0) >= 2:
+        o = orc.OracleEESDTree(si.weights_to_numpy(w), max_seq, kw["tree_width"], seed=kw.get("seed", 0), k_cap=k_cap,
+                               ts_update="literal" if kw.get("ts_update", 0) else "prose")
+    else:
+        o = orc.OracleEESD(si.weights_to_numpy(w), max_seq, temperature, seed=kw.get("seed", 0), k_cap=k_cap,
+                           ts_update="literal" if kw.get("ts_update", 0) else "prose")
     g = pk.EESD(si.weights_to_device(w, "cuda"), max_seq, temperature, k_cap=k_cap, **kw)
     return o, g
 

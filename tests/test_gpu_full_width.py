@@ -55,6 +55,40 @@ def test_full_width_reduced_depth_matches_oracle(name, n_prompt, ks):
         assert rel_err(k, ref.k[:n]) < TOL_BF16 and rel_err(v, ref.v[:n]) < TOL_BF16
 
 
+@pytest.mark.parametrize("name,width,K", [("13b", 2, 4), ("70b", 3, 5)])
+def test_full_width_tree_verify_matches_oracle(name, width, K):
+    """The candidate-tree block (9 and 16 rows) at full width and depth 2: node logits under the
+    tree mask against the oracle's path-by-path forwards, and the caches after the accepted
+    nodes moved into place."""
+    require_gpu()
+    base = si.LLAMA13B if name == "13b" else si.LLAMA70B
+    shape = si.reduced_depth(base, 2, 1)
+    o, g = make_pair(shape, 22, 128, 0.0, k_cap=K, jitter=0.05, gen_device="cuda", kv_page=64, tree_width=width)
+    prompt = si.make_prompt(60, shape["vocab"], 6)     # the 16-row block crosses the 64-token page boundary
+    t_ref = o.prefill(prompt)
+    g.prefill(prompt)
+    g.force_pending(t_ref)
+    kids = [o.draft_step_tree() for _ in range(K)]
+    g.force_drafts([t for k in kids for t in k])
+    for i in range(K):
+        g.draft_step(sync=False)
+    a, y, branch = o.verify_accept_tree()
+    g.verify()
+    assert rel_err(g.verify_logits(0), o.tree_logits[()]) < TOL_BF16
+    for i in range(1, K + 1):
+        for j in range(width):
+            assert rel_err(g.verify_logits(1 + (i - 1) * width + j), o.tree_logits[(i, j)]) < TOL_BF16, (i, j)
+    a_gpu, y_gpu = g.accept()
+    if (a_gpu, y_gpu) == (a, y):        # random weights: usually a = 0; the caches are checked either way
+        o.rollback_tree(a, y, branch)
+        g.rollback(a)
+        n = o.kv_len
+        for cache in range(3):
+            ref = o.kv[cache] if cache < 2 else o.ee_kv
+            k, v = g.kv(cache, n)
+            assert rel_err(k, ref.k[:n]) < TOL_BF16 and rel_err(v, ref.v[:n]) < TOL_BF16
+
+
 def test_full_depth_70b_properties():
     """80 layers, 64/8 heads, 2048-token cache: block verify == sequential steps, rollback keeps the cache."""
     require_gpu()
