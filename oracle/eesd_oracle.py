@@ -18,6 +18,8 @@ What follows which passage of the paper:
   output keeps the distribution of auto-regressive decoding
 * Beta posterior controller .............. Section 3.3 Eq. 2-4 and Algorithm 2 (Appendix A)
 * v_d, r_d, harmonic mean, speed model ... Section 4.1 "Metrics", Appendix D
+* calibrated controller .................. Section 3.3 "TS with Calibration", Eq. 5-8,
+  Algorithm 3 and the posterior derived in Appendix B
 * tree of draft candidates ............... Section 4.3 "Implement Tree Attention" and the
   caption of its table (a candidate is kept only if it is the target's top-1 token);
   the tree's shape is this file's reading, stated at OracleEESDTree
@@ -29,7 +31,10 @@ the transformer against an independent library implementation of the LLaMA
 decoder, closed forms of the Beta posterior, published vectors of the
 counter hash; for the candidate tree (tests/test_oracle_tree_pins.py): brute force
 over all root paths, equality with greedy auto-regressive decoding, from-scratch
-forwards of every path, caches after rollback.  Per-seed sampled token streams at temperature 1 are fixed by
+forwards of every path, caches after rollback; for the calibrated controller
+(tests/test_oracle_cali_pins.py): the posterior against numerical Bayes on a grid,
+the normal variates against the normal law, the predictor against a library
+two-class softmax, the running mean against a plain mean.  Per-seed sampled token streams at temperature 1 are fixed by
 nothing but this file: "parity unpinned" by the paper for those.
 
 Storage is float32 only where a value is *input data* (weights) or where the
@@ -264,6 +269,64 @@ class BetaTS:
 
 
 # ---------------------------------------------------------------------------
+# Thompson sampling with calibration (Section 3.3 "TS with Calibration", Eq. 5-8, Algorithm 3)
+# ---------------------------------------------------------------------------
+
+def normal_draw(seed: int, rnd: int, slot: int) -> float:
+    """Standard normal variate from two counter-based uniforms (Box-Muller, cosine branch).
+    math.* are the C library's routines, which the library's host code calls too."""
+    u1 = uniform(seed, STREAM_TS_THETA, rnd, slot, 0)
+    u2 = uniform(seed, STREAM_TS_THETA, rnd, slot, 1)
+    return math.sqrt(-2.0 * math.log(1.0 - u1)) * math.cos(2.0 * math.pi * u2)
+
+
+def cali_theta_m(cw: dict, h_target: np.ndarray, h_draft: np.ndarray, i: int) -> float:
+    """Eq. 5: theta_M = Sigmoid(W_p (W^i H_t^(T), H_{t+i}^(D))), i clipped to the number of W^i.
+    W_p has two rows and was trained with cross-entropy on chi in {0, 1}: the score is the
+    probability of class 1, i.e. the logistic function of the difference of the two outputs."""
+    W = cw["w"][min(i, cw["w"].shape[0]) - 1].astype(F64)
+    u = W @ h_target.astype(F64)
+    z = cw["wp"].astype(F64) @ np.concatenate([u, h_draft.astype(F64)])
+    return 1.0 / (1.0 + math.exp(-(float(z[1]) - float(z[0]))))
+
+
+class CaliTS:
+    """Gaussian posterior over theta: prior N(theta_M, sigma_M^2) from the predictor, n
+    verifications whose sample mean theta_hat has variance sigma_S^2 each (Eq. 6-7)."""
+
+    def __init__(self, sigma_m: float, sigma_s: float, theta_hat0: float, seed: int = 0, update: str = "judged"):
+        self.sigma_m, self.sigma_s, self.seed, self.update_mode = float(sigma_m), float(sigma_s), seed, update
+        self.theta_hat = float(theta_hat0)
+        self.n = 0            # verifications so far
+        self.weight = 1.0     # observations behind theta_hat; theta_hat0 counts as one (the "+1" of Eq. 8)
+
+    def posterior(self, theta_m: float) -> Tuple[float, float]:
+        sm2, ss2, n = self.sigma_m ** 2, self.sigma_s ** 2, self.n
+        mu = ss2 / (n * sm2 + ss2) * theta_m + n * sm2 / (n * sm2 + ss2) * self.theta_hat
+        var = sm2 * ss2 / (ss2 + n * sm2)
+        return mu, var
+
+    def decide(self, theta_m: float, rnd: int, slot: int) -> Tuple[float, bool]:
+        """Algorithm 3, steps 9-12: theta ~ N(mu, sigma^2), chi ~ Bernoulli(theta) (theta <= 0
+        never goes on, theta >= 1 always does)."""
+        mu, var = self.posterior(theta_m)
+        theta = mu + math.sqrt(var) * normal_draw(self.seed, rnd, slot)
+        return theta, uniform(self.seed, STREAM_TS_CHI, rnd, slot) < theta
+
+    def update(self, n_accepted: int, n_drafted: int) -> None:
+        """Algorithm 3, steps 21-22.  theta_hat is the observed mean of chi.  Eq. 8 as printed adds
+        |Q_v| successes for |Q_v| new observations, so it can only rise; 'judged' (default) counts
+        what the target judged, as the Beta controller does: a successes out of min(a + 1, K)
+        observations.  'printed' keeps the printed form with |Q_v| = a."""
+        a, K = n_accepted, n_drafted
+        self.n += 1
+        new = min(a + 1, K) if self.update_mode == "judged" else a
+        if new:
+            self.theta_hat = (self.theta_hat * self.weight + a) / (self.weight + new)
+            self.weight += new
+
+
+# ---------------------------------------------------------------------------
 # statistics (Section 4.1 "Metrics", Appendix D)
 # ---------------------------------------------------------------------------
 
@@ -353,6 +416,7 @@ class OracleEESD:
             x = decoder_layer(x, pos, self.kv[l], self.w["layers"][l], self.sh)
             if l + 1 == self.N:
                 self._ee_kv_fill(x, pos)
+        self.h_target_rows = x.copy()      # last-layer hidden states of the block (H^(T) of Eq. 5)
         h = rmsnorm(x, self.w["final_norm"], self.sh["rms_eps"])
         return h @ self.w["lm_head"].astype(F64).T
 
@@ -364,6 +428,7 @@ class OracleEESD:
         for l in range(self.N):
             x = decoder_layer(x, p, self.kv[l], self.w["layers"][l], self.sh)
         x = decoder_layer(x, p, self.ee_kv, self.w["ee_layer"], self.sh)
+        self.h_draft = x[0].copy()         # last-layer hidden state of the draft model (H^(D) of Eq. 5)
         h = rmsnorm(x, self.w["ee_norm"], self.sh["rms_eps"])
         return (h @ self.w["ee_head"].astype(F64).T)[0]
 
@@ -454,6 +519,40 @@ class OracleEESD:
             self.rollback(a, y)
             out.extend(committed)
             r += 1
+        out = out[:max_new]
+        self.stats.generated = len(out)
+        return out
+
+    def generate_cali(self, prompt: Sequence[int], max_new: int, cw: dict, cali: "CaliTS",
+                      trace: Optional[list] = None) -> List[int]:
+        """Algorithm 3: after every draft token the predictor scores the draft model's hidden
+        state against the target's hidden state at the last verified position, and the
+        calibrated posterior decides whether to draft on."""
+        out = [self.prefill(prompt)]
+        h_t = self.h_target_rows[-1]
+        while len(out) < max_new:
+            k_max = min(self.k_cap, max_new - len(out))
+            k, scores = 0, []
+            while True:
+                self.draft_step()
+                k += 1
+                if k >= k_max:
+                    break
+                theta_m = cali_theta_m(cw, h_t, self.h_draft, k)
+                theta, chi = cali.decide(theta_m, self.rnd, k)
+                scores.append((theta_m, theta, chi))
+                if not chi:
+                    break
+            self.verify()
+            a, y = self.accept()
+            if trace is not None:
+                trace.append(dict(K=k, a=a, y=y, drafts=list(self.drafts), scores=scores, n=cali.n, theta_hat=cali.theta_hat,
+                                  base=self.kv_len, h_t=h_t))
+            h_t = self.h_target_rows[a]        # the position whose output is the next pending token
+            committed = self.drafts[:a] + [y]
+            cali.update(a, k)
+            self.rollback(a, y)
+            out.extend(committed)
         out = out[:max_new]
         self.stats.generated = len(out)
         return out

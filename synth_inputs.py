@@ -150,6 +150,21 @@ def make_weights(shape: dict, seed: int, device="cpu", std: float = 0.02,
     return w
 
 
+def make_cali_weights(shape: dict, seed: int, device="cpu", n_mats: int = 10, spread: float = 8.0) -> dict:
+    """Random predictor of the calibrated controller: n_mats matrices [d][d] and one [2][2d]
+    (both [out][in]) in the model's storage type, scaled so that scores spread over (0, 1)."""
+    dtype = _torch_dtype(shape)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed) + 7919)
+    d = shape["d_model"]
+    return dict(w=_randn(gen, (n_mats, d, d), 1.0 / d ** 0.5, dtype, device),
+                wp=_randn(gen, (2, 2 * d), spread / (2 * d) ** 0.5, dtype, device))
+
+
+def cali_to_numpy(cw: dict) -> dict:
+    return {k: v.detach().to("cpu", torch.float32).numpy() for k, v in cw.items()}
+
+
 LAYER_KEYS = ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")
 
 
