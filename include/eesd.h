@@ -47,7 +47,7 @@ typedef enum eesd_status {
 } eesd_status;
 
 enum { EESD_DTYPE_F32 = 0, EESD_DTYPE_BF16 = 1 };
-enum { EESD_TS_BETA = 0, EESD_TS_FIXED = 1, EESD_TS_SCHEDULE = 2 };
+enum { EESD_TS_BETA = 0, EESD_TS_FIXED = 1, EESD_TS_SCHEDULE = 2, EESD_TS_CALI = 3 };
 enum { EESD_GEMM_AUTO = 0, EESD_GEMM_VALU = 1, EESD_GEMM_MFMA = 2 };
 
 typedef struct eesd_config {
@@ -71,7 +71,8 @@ typedef struct eesd_config {
     double ts_alpha0;        /* prior Beta(alpha0, beta0) of the controller (Algorithm 2, step 1) */
     double ts_beta0;
     int32_t ts_mode;         /* EESD_TS_BETA: Algorithm 2; EESD_TS_FIXED: always k_cap drafts
-                                (the "w/o TS" ablation); EESD_TS_SCHEDULE: eesd_set_draft_schedule */
+                                (the "w/o TS" ablation); EESD_TS_SCHEDULE: eesd_set_draft_schedule;
+                                EESD_TS_CALI: Algorithm 3 (needs eesd_set_calibration) */
     int32_t ts_update;       /* reading of Eq. 3-4: 0: r = a, n = min(a+1, K) (drafts the target judged);
                                 1: |Q_v| = a+1 taken literally, r = a, n = min(a+2, K) */
     int32_t gemm_path;       /* EESD_GEMM_*: AUTO picks per pass; the others force one kernel family */
@@ -206,6 +207,38 @@ int eesd_host_draw_k(double alpha, double beta, uint64_t seed, int64_t round, in
 /* Posterior update of Eq. 3-4 in place (reading as eesd_config.ts_update). */
 int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t n_drafted, int32_t reading);
 
+/* ---- Thompson sampling with calibration (Section 3.3 Eq. 5-8, Algorithm 3) ------------ */
+/* The predictor of Eq. 5 and the hyper-parameters of the Gaussian posterior.  w and wp are DEVICE
+ * pointers, BORROWED until eesd_destroy, row-major [out][in] in the model's storage type. */
+typedef struct eesd_calibration {
+    const void* w;       /* W^1..W^n_mats: [n_mats][d_model][d_model]; draft step i uses W^min(i, n_mats) */
+    const void* wp;      /* W_p: [2][2 d_model]; its input is (W^i H_t^(T), H_{t+i}^(D)) */
+    int32_t n_mats;      /* 1..10 */
+    int32_t update;      /* reading of Eq. 8: 0: theta_hat is the mean of the chi the target judged (a successes out of
+                            min(a+1, K)); 1: as printed (a successes out of a) */
+    double sigma_m;      /* > 0: standard deviation of the predictor's error */
+    double sigma_s;      /* > 0: standard deviation of a round's sample mean */
+    double theta_hat0;   /* initial observed mean; counts as one observation */
+} eesd_calibration;
+
+/* Installs the predictor; required before the first round when ts_mode == EESD_TS_CALI (any
+ * ts_mode may install it to use eesd_cali_score).  Resets the controller's observations. */
+int eesd_set_calibration(eesd_ctx* ctx, const eesd_calibration* cal);
+
+/* Eq. 5 for the draft step just made (i = drafts since the last rollback >= 1):
+ * theta_M = logistic(z_1 - z_0), z = W_p (W^min(i,n_mats) H_t^(T), H^(D)), where H_t^(T) is the target's
+ * last-layer hidden state at the last verified position (the one whose output is the pending
+ * token) and H^(D) the draft model's last-layer hidden state of this step.  Synchronises. */
+int eesd_cali_score(eesd_ctx* ctx, float* theta_m);
+
+/* Host-only parts of Algorithm 3 (no GPU needed).
+ * decide: mu, sigma^2 by Eq. 6-7 from (theta_m, theta_hat, n verifications), theta = mu + sigma z with z
+ * a Box-Muller normal of the context's counter-based uniforms (stream TS_THETA, subs 0 and 1),
+ * chi = u < theta with u of stream TS_CHI.  update: Eq. 8 in the chosen reading, n += 1. */
+int eesd_host_cali_decide(double sigma_m, double sigma_s, double theta_hat, int64_t n, double theta_m, uint64_t seed,
+                          int64_t round, int32_t slot, double* theta, int32_t* chi);
+int eesd_host_cali_update(double* theta_hat, double* weight, int64_t* n, int32_t n_accepted, int32_t n_drafted, int32_t reading);
+
 /* ---- test and benchmark hooks ------------------------------------------------------- */
 enum {
     EESD_READ_DRAFT_LOGITS = 0,  /* index = draft slot i (0-based): vocab floats */
@@ -216,7 +249,8 @@ enum {
     EESD_READ_TOKENS = 5,        /* the block [pending, d_1..d_K] as int32 */
     EESD_READ_KV_LEN = 6,        /* one int32 */
     EESD_READ_PAGE_TABLE = 7,    /* ceil(max_seq / kv_page) int32 (-1 = unmapped) */
-    EESD_READ_TREE_TOKENS = 8    /* tree mode: the tokens of the block's 1 + K * tree_width rows as int32 */
+    EESD_READ_TREE_TOKENS = 8,   /* tree mode: the tokens of the block's 1 + K * tree_width rows as int32 */
+    EESD_READ_CALI_STATE = 9     /* three doubles: theta_hat, the observations behind it, verifications n */
 };
 /* Copies internal state to HOST memory as fp32 / int32.  Synchronises.  n_tokens limits KV reads. */
 int eesd_debug_read(eesd_ctx* ctx, int what, int index, int32_t n_tokens, void* host_dst, size_t bytes);

@@ -13,9 +13,9 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 DTYPE_F32, DTYPE_BF16 = 0, 1
-TS_BETA, TS_FIXED, TS_SCHEDULE = 0, 1, 2
+TS_BETA, TS_FIXED, TS_SCHEDULE, TS_CALI = 0, 1, 2, 3
 GEMM_AUTO, GEMM_VALU, GEMM_MFMA = 0, 1, 2
-READ_DRAFT_LOGITS, READ_DRAFT_PROBS, READ_VERIFY_LOGITS, READ_KV_K, READ_KV_V, READ_TOKENS, READ_KV_LEN, READ_PAGE_TABLE, READ_TREE_TOKENS = range(9)
+READ_DRAFT_LOGITS, READ_DRAFT_PROBS, READ_VERIFY_LOGITS, READ_KV_K, READ_KV_V, READ_TOKENS, READ_KV_LEN, READ_PAGE_TABLE, READ_TREE_TOKENS, READ_CALI_STATE = range(10)
 
 _STATUS = {0: "EESD_OK", -1: "EESD_EINVAL", -2: "EESD_ENOMEM", -3: "EESD_ESTATE", -4: "EESD_ERANGE", -5: "EESD_EDEVICE"}
 
@@ -33,6 +33,11 @@ class _Config(C.Structure):
                 ("kv_page", C.c_int32), ("k_cap", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
                 ("ts_alpha0", C.c_double), ("ts_beta0", C.c_double), ("ts_mode", C.c_int32), ("ts_update", C.c_int32),
                 ("gemm_path", C.c_int32), ("tree_width", C.c_int32)]
+
+
+class _Calibration(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("wp", C.c_void_p), ("n_mats", C.c_int32), ("update", C.c_int32),
+                ("sigma_m", C.c_double), ("sigma_s", C.c_double), ("theta_hat0", C.c_double)]
 
 
 class _Layer(C.Structure):
@@ -75,7 +80,8 @@ _LIB = None
 EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_accepted_tokens", "eesd_rollback",
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
-           "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
+           "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_set_calibration", "eesd_cali_score",
+           "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
 
 
 def lib() -> C.CDLL:
@@ -115,6 +121,11 @@ def lib() -> C.CDLL:
     L.eesd_host_uniform.restype = C.c_double
     L.eesd_host_draw_k.argtypes = [C.c_double, C.c_double, C.c_uint64, C.c_int64, I32]
     L.eesd_host_ts_update.argtypes = [P(C.c_double), P(C.c_double), I32, I32, I32]
+    L.eesd_set_calibration.argtypes = [VP, P(_Calibration)]
+    L.eesd_cali_score.argtypes = [VP, P(C.c_float)]
+    L.eesd_host_cali_decide.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int64, C.c_double, C.c_uint64, C.c_int64, I32,
+                                        P(C.c_double), P(I32)]
+    L.eesd_host_cali_update.argtypes = [P(C.c_double), P(C.c_double), P(C.c_int64), I32, I32, I32]
     L.eesd_op_accept.argtypes = [VP, VP, VP, P(C.c_double), I32, I32, I32, VP, P(I32)]
     L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
     L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, VP]
@@ -150,6 +161,22 @@ def host_ts_update(alpha: float, beta: float, n_accepted: int, n_drafted: int, r
     if rc:
         raise EesdError(rc, "eesd_host_ts_update")
     return a.value, b.value
+
+
+def host_cali_decide(sigma_m: float, sigma_s: float, theta_hat: float, n: int, theta_m: float, seed: int, rnd: int, slot: int):
+    theta, chi = C.c_double(), C.c_int32()
+    rc = lib().eesd_host_cali_decide(sigma_m, sigma_s, theta_hat, n, theta_m, seed, rnd, slot, C.byref(theta), C.byref(chi))
+    if rc:
+        raise EesdError(rc, "eesd_host_cali_decide")
+    return theta.value, bool(chi.value)
+
+
+def host_cali_update(theta_hat: float, weight: float, n: int, n_accepted: int, n_drafted: int, reading: int = 0):
+    th, w, nn = C.c_double(theta_hat), C.c_double(weight), C.c_int64(n)
+    rc = lib().eesd_host_cali_update(C.byref(th), C.byref(w), C.byref(nn), n_accepted, n_drafted, reading)
+    if rc:
+        raise EesdError(rc, "eesd_host_cali_update")
+    return th.value, w.value, nn.value
 
 
 def set_tunable(name: str, value: int) -> None:
@@ -251,6 +278,21 @@ class EESD:
     def set_draft_schedule(self, ks) -> None:
         k = _i32(ks)
         self._ck(lib().eesd_set_draft_schedule(self._h, _ptr(k, C.c_int32), len(k)))
+
+    def set_calibration(self, cw: dict, sigma_m: float, sigma_s: float, theta_hat0: float, update: int = 0) -> None:
+        """cw: {"w": [n_mats][d][d], "wp": [2][2d]} torch tensors on the GPU in the model's dtype (borrowed, kept alive here)."""
+        self._cali_keep = cw
+        cal = _Calibration(cw["w"].data_ptr(), cw["wp"].data_ptr(), int(cw["w"].shape[0]), update, sigma_m, sigma_s, theta_hat0)
+        self._ck(lib().eesd_set_calibration(self._h, C.byref(cal)))
+
+    def cali_score(self) -> float:
+        th = C.c_float()
+        self._ck(lib().eesd_cali_score(self._h, C.byref(th)))
+        return th.value
+
+    def cali_state(self):
+        a = self._read(READ_CALI_STATE, 0, 0, np.empty(3, np.float64))
+        return float(a[0]), float(a[1]), int(a[2])
 
     def next_draft_len(self, k_max: int) -> int:
         k = C.c_int32()

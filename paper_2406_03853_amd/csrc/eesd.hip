@@ -20,10 +20,11 @@
 #include "sampling.hiph"
 
 #define MAX_ROWS 16    // rows of a decoding pass: 1 (draft) .. k_cap + 1 (verify; 1 + k_cap * width in tree mode)
-// pinned result words: [0] a, [1] y, [2] draft token, [3] token hooks, [4..4+MAX_ROWS) accepted rows, [24..24+MAX_ROWS+1) block tokens
+// pinned result words: [0] a, [1] y, [2] draft token, [3] token hooks, [4..4+MAX_ROWS) accepted rows, [24..24+MAX_ROWS+1) block tokens, [44] theta_M (float)
 #define H_RESULT_INTS 48
 #define H_ROWS_AT 4
 #define H_TOKS_AT 24
+#define H_THETA_AT 44
 #define PREFILL_ROWS 128  // rows of a prefill block when the tiled MFMA product applies
 
 // ---------------------------------------------------------------------------------------------
@@ -121,6 +122,13 @@ struct eesd_ctx {
     unsigned short tree_mask[16];   // visible block rows per row
     unsigned char tree_depth[16];   // rotary offset per row
     std::vector<int32_t> last_tokens;   // tokens the last accept kept (drafts or tree nodes), without the next token
+    // calibrated controller (Algorithm 3)
+    bool cali_set;
+    eesd_calibration cali;
+    double cali_theta_hat, cali_weight;   // observed mean of chi and the observations behind it
+    int64_t cali_n;                       // verifications so far
+    float *h_t, *cali_u, *theta_dev;      // H_t^(T) [d], W^i H_t^(T) [d], theta_M
+    bf16_t* h_tb;                         // bf16 copy of h_t (operand of the MFMA product)
     int max_splits;
     int row_cap;           // rows the activation buffers hold (16, or PREFILL_ROWS)
     hipEvent_t ev[4];
@@ -690,6 +698,34 @@ static int draw_k(eesd_ctx* c, int k_max) {
 
 static void ts_update(eesd_ctx* c, int a, int K) { beta_ts_update(&c->alpha, &c->beta, a, K, c->cfg.ts_update); }
 
+// ---- calibrated controller (Section 3.3 Eq. 6-8, Algorithm 3), host side ----
+// standard normal from two counter-based uniforms (Box-Muller, cosine branch)
+static double normal_draw(uint64_t seed, int64_t rnd, int slot) {
+    const double u1 = uniform53(seed, STREAM_TS_THETA, rnd, slot, 0), u2 = uniform53(seed, STREAM_TS_THETA, rnd, slot, 1);
+    return sqrt(-2.0 * log(1.0 - u1)) * cos(2.0 * M_PI * u2);
+}
+
+// theta ~ N(mu, sigma^2) with the posterior of Eq. 6-7; chi ~ Bernoulli(theta)
+static bool cali_decide(double sigma_m, double sigma_s, double theta_hat, int64_t n, double theta_m, uint64_t seed, int64_t rnd, int slot,
+                        double* theta_out) {
+    const double sm2 = sigma_m * sigma_m, ss2 = sigma_s * sigma_s, dn = (double)n;
+    const double mu = ss2 / (dn * sm2 + ss2) * theta_m + dn * sm2 / (dn * sm2 + ss2) * theta_hat;
+    const double var = sm2 * ss2 / (ss2 + dn * sm2);
+    const double theta = mu + sqrt(var) * normal_draw(seed, rnd, slot);
+    if (theta_out) *theta_out = theta;
+    return uniform53(seed, STREAM_TS_CHI, rnd, slot, 0) < theta;
+}
+
+// Eq. 8: running mean of the observed chi (reading 0: what the target judged; 1: as printed)
+static void cali_update(double* theta_hat, double* weight, int64_t* n, int a, int K, int reading) {
+    *n += 1;
+    const int fresh = reading == 0 ? std::min(a + 1, K) : a;
+    if (fresh) {
+        *theta_hat = (*theta_hat * *weight + (double)a) / (*weight + (double)fresh);
+        *weight += (double)fresh;
+    }
+}
+
 // Host-only entry points (no GPU needed): the controller and the uniform generator as the
 // library uses them, so that they can be checked without a device.
 extern "C" double eesd_host_uniform(uint64_t seed, int32_t stream, int64_t round, int32_t slot, int32_t sub) {
@@ -702,6 +738,18 @@ extern "C" int eesd_host_draw_k(double alpha, double beta, uint64_t seed, int64_
 extern "C" int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t n_drafted, int32_t reading) {
     if (!alpha || !beta || n_accepted < 0 || n_accepted > n_drafted || reading < 0 || reading > 1) return EESD_EINVAL;
     beta_ts_update(alpha, beta, n_accepted, n_drafted, reading);
+    return EESD_OK;
+}
+
+extern "C" int eesd_host_cali_decide(double sigma_m, double sigma_s, double theta_hat, int64_t n, double theta_m, uint64_t seed,
+                                     int64_t round, int32_t slot, double* theta, int32_t* chi) {
+    if (!chi || !(sigma_m > 0.0) || !(sigma_s > 0.0) || n < 0) return EESD_EINVAL;
+    *chi = cali_decide(sigma_m, sigma_s, theta_hat, n, theta_m, seed, round, slot, theta) ? 1 : 0;
+    return EESD_OK;
+}
+extern "C" int eesd_host_cali_update(double* theta_hat, double* weight, int64_t* n, int32_t n_accepted, int32_t n_drafted, int32_t reading) {
+    if (!theta_hat || !weight || !n || n_accepted < 0 || n_drafted < n_accepted || reading < 0 || reading > 1) return EESD_EINVAL;
+    cali_update(theta_hat, weight, n, n_accepted, n_drafted, reading);
     return EESD_OK;
 }
 
@@ -730,7 +778,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
-                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk};
+                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb};
     for (void* p : dev)
         if (p) hipFree(p);
     if (c->h_table) hipHostFree(c->h_table);
@@ -752,7 +800,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if (g.kv_page < 16 || (g.kv_page & (g.kv_page - 1))) return EESD_EINVAL;
     if (g.dtype != EESD_DTYPE_F32 && g.dtype != EESD_DTYPE_BF16) return EESD_EINVAL;
     if (!(g.temperature >= 0.0f) || !(g.ts_alpha0 > 0.0) || !(g.ts_beta0 > 0.0)) return EESD_EINVAL;
-    if (g.ts_mode < 0 || g.ts_mode > 2 || g.ts_update < 0 || g.ts_update > 1 || g.gemm_path < 0 || g.gemm_path > 2) return EESD_EINVAL;
+    if (g.ts_mode < 0 || g.ts_mode > 3 || g.ts_update < 0 || g.ts_update > 1 || g.gemm_path < 0 || g.gemm_path > 2) return EESD_EINVAL;
     if (g.tree_width < 0 || g.tree_width > TREE_MAX_WIDTH) return EESD_EINVAL;
     if (g.tree_width >= 2 && (g.temperature != 0.0f || 1 + g.k_cap * g.tree_width > MAX_ROWS)) return EESD_EINVAL;
     const int vec = g.dtype == EESD_DTYPE_BF16 ? 8 : 4;
@@ -792,6 +840,9 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->xb_has_ssq = false;
     c->xb = c->ab = c->actb = nullptr;
     c->blk_tok = c->prompt_dev = c->result_dev = c->tree_blk = nullptr;
+    c->h_t = c->cali_u = c->theta_dev = nullptr; c->h_tb = nullptr;
+    c->cali_set = false; memset(&c->cali, 0, sizeof c->cali);
+    c->cali_theta_hat = 0.0; c->cali_weight = 1.0; c->cali_n = 0;
     c->tree_active = false;
     c->h_result = c->h_prompt = nullptr;
     for (auto& e : c->ev) e = nullptr;
@@ -851,6 +902,10 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if ((rc = dev_alloc(c, &c->prompt_dev, (size_t)g.max_seq))) return bail(rc);
     if ((rc = dev_alloc(c, &c->result_dev, (size_t)2 + MAX_ROWS))) return bail(rc);
     if ((rc = dev_alloc(c, &c->tree_blk, (size_t)MAX_ROWS + 1))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->h_t, (size_t)g.d_model))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->cali_u, (size_t)g.d_model))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->theta_dev, (size_t)4))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->h_tb, (size_t)g.d_model))) return bail(rc);
     // rows of the bf16 activation buffers past M are read (and ignored) by the MFMA product
     hipMemset(c->xb, 0, sizeof(bf16_t) * R * d);
     hipMemset(c->ab, 0, sizeof(bf16_t) * R * qd);
@@ -899,6 +954,15 @@ static hipError_t smp_allow(F fn, int V) { return allow_lds((const void*)fn, smp
 static float inv_temperature(const eesd_ctx* c) { return c->cfg.temperature > 0.f ? 1.0f / c->cfg.temperature : 1.0f; }
 static int greedy(const eesd_ctx* c) { return c->cfg.temperature == 0.f; }
 
+// The predictor's H_t^(T): row `row` of the hidden states the last target pass left in c->x.
+static int save_target_hidden(eesd_ctx* c, int row) {
+    if (!c->cali_set) return EESD_OK;
+    const int d = c->cfg.d_model;
+    hipLaunchKernelGGL(save_hidden_kernel, dim3((d + 255) / 256), dim3(256), 0, c->stream, c->x + (size_t)row * d, c->h_t, c->h_tb, d);
+    HIP_TRY(c, hipGetLastError());
+    return EESD_OK;
+}
+
 static int tree_width(const eesd_ctx* c) { return c->cfg.tree_width >= 2 ? c->cfg.tree_width : 1; }
 // most rows a verify block can have
 static int rows_cap(const eesd_ctx* c) { return 1 + c->cfg.k_cap * tree_width(c); }
@@ -909,6 +973,7 @@ static void reset_sequence(eesd_ctx* c) {
     c->alpha = c->cfg.ts_alpha0; c->beta = c->cfg.ts_beta0;
     c->forced.clear(); c->forced_pos = 0;
     memset(&c->stats, 0, sizeof c->stats);
+    c->cali_theta_hat = c->cali.theta_hat0; c->cali_weight = 1.0; c->cali_n = 0;
 }
 
 extern "C" int eesd_prefill(eesd_ctx* c, const int32_t* prompt, int32_t n, int32_t* first_token) {
@@ -934,6 +999,7 @@ extern "C" int eesd_prefill(eesd_ctx* c, const int32_t* prompt, int32_t n, int32
         if (rc) return rc;
         last_m = m;
     }
+    if ((rc = save_target_hidden(c, last_m - 1))) return rc;
     // logits of the last prompt position only (the family of the last block left its input ready)
     rc = run_head(c, c->w.final_norm, c->w.lm_head, last_m - 1, 1, c->logits, last_mfma);
     if (rc) return rc;
@@ -1116,6 +1182,13 @@ extern "C" int eesd_rollback(eesd_ctx* c, int32_t n_accepted) {
     if (tree_width(c) > 1 && n_accepted > c->last_a)
         return fail(c, EESD_ERANGE, "rollback: tree mode keeps at most the %d accepted nodes", c->last_a);
     // the stream is idle here: eesd_accept synchronised it
+    {   // the hidden state whose output is the next pending token: verify row of the last kept node
+        int row = n_accepted;
+        if (tree_width(c) > 1) row = n_accepted ? c->h_result[H_ROWS_AT + n_accepted - 1] : 0;
+        int rc = save_target_hidden(c, row);
+        if (rc) return rc;
+        if (c->cali_set) cali_update(&c->cali_theta_hat, &c->cali_weight, &c->cali_n, n_accepted, K, c->cali.update);
+    }
     c->kv_len += n_accepted + 1;
     release_pages(c, c->kv_len);
     // the pending token of the next round is already in blk_tok[0]: the accept kernel stored it
@@ -1126,6 +1199,44 @@ extern "C" int eesd_rollback(eesd_ctx* c, int32_t n_accepted) {
     c->n_drafted = 0;
     c->round += 1;
     c->state = ST_READY;
+    return EESD_OK;
+}
+
+extern "C" int eesd_set_calibration(eesd_ctx* c, const eesd_calibration* cal) {
+    if (!c) return EESD_EINVAL;
+    if (!cal || !cal->w || !cal->wp) return fail(c, EESD_EINVAL, "set_calibration: null pointer");
+    if (cal->n_mats < 1 || cal->n_mats > 10 || cal->update < 0 || cal->update > 1) return fail(c, EESD_EINVAL, "set_calibration: n_mats or update out of range");
+    if (!(cal->sigma_m > 0.0) || !(cal->sigma_s > 0.0) || !(cal->theta_hat0 == cal->theta_hat0))
+        return fail(c, EESD_EINVAL, "set_calibration: sigma_m and sigma_s must be positive");
+    if (c->state != ST_CREATED && !(c->state == ST_READY && c->n_drafted == 0))
+        return fail(c, EESD_ESTATE, "set_calibration: not between rounds");
+    c->cali = *cal;
+    c->cali_set = true;
+    c->cali_theta_hat = cal->theta_hat0; c->cali_weight = 1.0; c->cali_n = 0;
+    return EESD_OK;
+}
+
+extern "C" int eesd_cali_score(eesd_ctx* c, float* theta_m) {
+    if (!c) return EESD_EINVAL;
+    if (!theta_m) return fail(c, EESD_EINVAL, "cali_score: null pointer");
+    if (!c->cali_set) return fail(c, EESD_ESTATE, "cali_score: no predictor installed");
+    if (c->state != ST_READY || c->n_drafted < 1) return fail(c, EESD_ESTATE, "cali_score: no draft step made");
+    const eesd_config& g = c->cfg;
+    const int d = g.d_model, mat = std::min(c->n_drafted, (int)c->cali.n_mats) - 1;
+    const bool mfma = pick_mfma(c, 1);
+    const char* W = (const char*)c->cali.w + (size_t)mat * d * d * c->elem;
+    GemmP p = mfma ? gemm_base(W, c->h_tb, d, 1, d, d) : gemm_base(W, c->h_t, d, 1, d, d);   // no norm: the hidden state as it is
+    p.Y = c->cali_u; p.ldy = d;
+    int rc = gemm_launch<EPI_PLAIN>(c, mfma, p);
+    if (rc) return rc;
+    // c->x row 0 still holds the hidden state the early-exit layer left for this draft step
+    if (is_bf16(c)) hipLaunchKernelGGL((cali_score_kernel<bf16_t>), dim3(1), dim3(SMP_THREADS), 0, c->stream, (const bf16_t*)c->cali.wp, c->cali_u, c->x, d, c->theta_dev);
+    else hipLaunchKernelGGL((cali_score_kernel<float>), dim3(1), dim3(SMP_THREADS), 0, c->stream, (const float*)c->cali.wp, c->cali_u, c->x, d, c->theta_dev);
+    HIP_TRY(c, hipGetLastError());
+    float* h_theta = (float*)(c->h_result + H_THETA_AT);
+    HIP_TRY(c, hipMemcpyAsync(h_theta, c->theta_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    *theta_m = *h_theta;
     return EESD_OK;
 }
 
@@ -1158,6 +1269,7 @@ extern "C" int eesd_generate(eesd_ctx* c, const int32_t* prompt, int32_t n_promp
     const eesd_config& g = c->cfg;
     if (n_prompt + max_new + rows_cap(c) > g.max_seq)
         return fail(c, EESD_ERANGE, "generate: %d prompt + %d new + a verify block of %d rows exceeds max_seq %d", n_prompt, max_new, rows_cap(c), g.max_seq);
+    if (g.ts_mode == EESD_TS_CALI && !c->cali_set) return fail(c, EESD_ESTATE, "generate: ts_mode is EESD_TS_CALI but no predictor is installed");
     auto t_begin = std::chrono::steady_clock::now();
     int32_t tok;
     int rc = eesd_prefill(c, prompt, n_prompt, &tok);
@@ -1167,10 +1279,20 @@ extern "C" int eesd_generate(eesd_ctx* c, const int32_t* prompt, int32_t n_promp
     out[n++] = tok;
     double ms_d = 0, ms_v = 0, ms_a = 0;
     while (n < max_new) {
-        const int K = draw_k(c, std::min((int)g.k_cap, max_new - n));
+        const int k_max = std::min((int)g.k_cap, max_new - n);
+        const bool cali = g.ts_mode == EESD_TS_CALI;
+        const int K = cali ? k_max : draw_k(c, k_max);
         HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
-        for (int i = 0; i < K; ++i)
+        for (int i = 0; i < K; ++i) {
             if ((rc = eesd_draft_step(c, nullptr))) return rc;
+            if (cali && i + 1 < k_max) {
+                // Algorithm 3: the predictor scores this step, the calibrated posterior decides whether to go on
+                float theta_m;
+                if ((rc = eesd_cali_score(c, &theta_m))) return rc;
+                if (!cali_decide(c->cali.sigma_m, c->cali.sigma_s, c->cali_theta_hat, c->cali_n, (double)theta_m, g.seed, c->round, i + 1, nullptr))
+                    break;
+            }
+        }
         HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
         if ((rc = eesd_verify(c))) return rc;
         HIP_TRY(c, hipEventRecord(c->ev[2], c->stream));
@@ -1322,6 +1444,12 @@ extern "C" int eesd_debug_read(eesd_ctx* c, int what, int index, int32_t n_token
             size_t need = sizeof(int32_t) * (1 + c->n_drafted * tree_width(c));
             if (tree_width(c) < 2 || bytes < need) return fail(c, EESD_ERANGE, "debug_read: not in tree mode or destination too small");
             HIP_TRY(c, hipMemcpy(host_dst, c->tree_blk, need, hipMemcpyDeviceToHost));
+            return EESD_OK;
+        }
+        case EESD_READ_CALI_STATE: {
+            if (bytes < 3 * sizeof(double)) return fail(c, EESD_ERANGE, "debug_read: destination too small");
+            double* dst = (double*)host_dst;
+            dst[0] = c->cali_theta_hat; dst[1] = c->cali_weight; dst[2] = (double)c->cali_n;
             return EESD_OK;
         }
         case EESD_READ_KV_LEN: {

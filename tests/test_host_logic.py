@@ -46,3 +46,36 @@ def test_non_integer_posterior_keeps_the_law_of_k():
     assert stats.chisquare(got, want * n).pvalue > 1e-3
     with pytest.raises(pk.EesdError):
         pk.host_draw_k(0.0, 1.0, 0, 0, 4)
+
+
+def test_calibrated_controller_decisions_match_the_oracle():
+    """Section 3.3 Eq. 6-7, Algorithm 3 steps 9-12 on the host: same posterior, same normal variate
+    (both sides call the C library's log / cos / sqrt), same decision."""
+    flips = 0
+    for sm, ss in ((0.2, 0.5), (0.05, 1.0), (0.7, 0.1)):
+        for seed in (0, 123456789):
+            c = orc.CaliTS(sm, ss, 0.4, seed=seed)
+            for n in (0, 1, 5, 60):
+                c.n = n
+                for rnd in range(1, 40):
+                    for slot in (1, 2, 9):
+                        theta_m = 0.05 + 0.9 * orc.uniform(7, 1, rnd, slot)
+                        want_theta, want_chi = c.decide(theta_m, rnd, slot)
+                        theta, chi = pk.host_cali_decide(sm, ss, c.theta_hat, n, theta_m, seed, rnd, slot)
+                        assert abs(theta - want_theta) <= 1e-15 * max(1.0, abs(want_theta))
+                        if abs(want_theta - orc.uniform(seed, orc.STREAM_TS_CHI, rnd, slot)) > 1e-12:
+                            assert chi == want_chi
+                        flips += chi
+    assert 0 < flips
+
+
+def test_calibrated_controller_update_matches_both_readings():
+    for mode, reading in (("judged", 0), ("printed", 1)):
+        c = orc.CaliTS(0.2, 0.5, 0.35, update=mode)
+        th, w, n = 0.35, 1.0, 0
+        for a, K in [(0, 3), (2, 2), (1, 4), (0, 1), (5, 5), (3, 7), (0, 2)]:
+            c.update(a, K)
+            th, w, n = pk.host_cali_update(th, w, n, a, K, reading)
+            assert (th, w, n) == (c.theta_hat, c.weight, c.n)
+    with pytest.raises(pk.EesdError):
+        pk.host_cali_update(0.5, 1.0, 0, 3, 2, 0)
