@@ -258,14 +258,14 @@ template <int EPI>
 static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
     // Which kernel (measured per product at the 13B and 70B shapes): one workgroup per tile streams
     // fastest for few rows and for the products with few tiles (QKV, attention output, FFN down) at
-    // any M <= 16; from about 6 rows on the products with many tiles (gate/up, LM heads) gain more
+    // any M <= 16; from 6 rows on (7 for the widest) the products with many tiles (gate/up, LM heads) gain more
     // from sharing the activation operand through LDS than they lose to its barriers, with 8 tiles
     // per workgroup when there are very many.  Prefill blocks (M > 16) always take the tile kernel.
     const int n_tiles16 = p.out_rows / 16;
     const bool partial = EPI == EPI_RESID && p.y_partial;
     bool use_tile = p.M > 16;
     if (p.M <= 16 && g_mfma_tile == 1) use_tile = true;
-    if (p.M <= 16 && g_mfma_tile == 0) use_tile = p.M >= 6 && n_tiles16 >= 1536 && !partial;
+    if (p.M <= 16 && g_mfma_tile == 0) use_tile = p.M >= (n_tiles16 >= 3072 ? 7 : 6) && n_tiles16 >= 1536 && !partial;
     if (EPI == EPI_RESID && p.xb_out) use_tile = false;   // the hand-over to the next product lives in the per-tile kernel
     if (use_tile && tile_shape_ok(p.out_rows, p.in_dim)) {
         if (p.M <= 16) {
