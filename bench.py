@@ -242,6 +242,14 @@ def main():
                    "hm": 200.0 * v_d * r_d / (v_d + r_d) if v_d + r_d else 0.0,
                    "ts_alpha": st.alpha, "ts_beta": st.beta, "weight_init_s": t_weights},
     }
+    # context only: the speed model of the paper's Appendix D, speedup = v_d / ((alpha - v_d) r_d + v_d) with
+    # alpha = T_draft / T_target, at the acceptance the paper reports for its TRAINED early-exit layers
+    # (Gsm8k, Beta-TS) and at this run's measured pass times (T_target taken as one verify pass)
+    if ms_draft and ms_verify:
+        alpha = ms_draft / ms_verify
+        vd_p, rd_p = (0.52, 0.68) if shape["d_model"] >= 8192 else (0.50, 0.67)
+        out["passes"]["alpha_Td_over_Tt"] = alpha
+        out["passes"]["speed_model_at_paper_acceptance"] = {"v_d": vd_p, "r_d": rd_p, "speedup_vs_autoregressive": vd_p / ((alpha - vd_p) * rd_p + vd_p)}
     if args.latency_sweep:
         out["latency_vs_K"] = latency_sweep(ctx, torch, sweep_tokens, k_cap, b_draft, shape, si)
     if not args.no_cpu_baseline:
