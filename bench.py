@@ -127,6 +127,8 @@ def main():
     ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--tree-width", type=int, default=0,
                     help="2..4: candidate-tree verification (greedy decoding; temperature is set to 0 and K is capped so that 1 + K * width <= 16)")
+    ap.add_argument("--verify-reuse", action="store_true",
+                    help="verify takes the drafted rows' layer-N hidden states from the draft steps instead of recomputing them")
     ap.add_argument("--controller", default="beta", choices=["beta", "cali"],
                     help="beta: Beta-posterior Thompson sampling (Algorithm 2); cali: the calibrated controller "
                          "(Algorithm 3) with a random predictor - measures its cost, not the paper's gain")
@@ -166,7 +168,7 @@ def main():
     if args.latency_sweep:
         max_seq = max(max_seq, sweep_tokens + k_cap + 2)
     max_seq = (max_seq + 63) // 64 * 64
-    ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64, tree_width=args.tree_width,
+    ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64, tree_width=args.tree_width, verify_reuse=int(args.verify_reuse),
                   ts_mode=pk.TS_CALI if args.controller == "cali" else pk.TS_BETA)
     if args.controller == "cali":
         ctx.set_calibration(si.make_cali_weights(shape, wseed, device="cuda"), 0.2, 0.5, 0.5)
@@ -226,6 +228,7 @@ def main():
                                f"prompt {n_prompt} uniform ids (a different one per step), {max_new} new tokens, Beta-TS K cap {k_cap}, "
                                f"temperature {args.temperature:g}, batch 1"
                                + (f", candidate tree of width {args.tree_width}" if args.tree_width >= 2 else "")
+                               + (", verify reuses the draft steps' layer-N hidden states" if args.verify_reuse else "")
                                + (", calibrated controller with a random predictor" if args.controller == "cali" else "")
                                + (f", draft correlated with the target (gamma {args.draft_correlation:g})" if args.draft_correlation is not None else ""),
                    "prefill": "included in every step (128-row blocks, tiled MFMA product)" if bf16 else "included in every step (16-row blocks)"},

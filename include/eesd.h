@@ -81,6 +81,11 @@ typedef struct eesd_config {
                                 the first is drafted on from, the others are leaves; one verify pass judges all
                                 1 + K * tree_width rows under a tree mask and keeps only candidates that are the
                                 target's top-1 token.  Needs temperature == 0 and 1 + k_cap * tree_width <= 16 */
+    int32_t verify_reuse;    /* 1: eesd_verify takes the layer-N hidden states of rows 0..K-1 from the draft steps that
+                                computed them (Section 3.1: the draft model IS the target's first N layers) and runs
+                                layers 1..N for the last draft token only; 0: all L layers on all K+1 rows.  Same
+                                result up to rounding; ignored in tree mode */
+    int32_t reserved;        /* 0 */
 } eesd_config;
 
 /* One decoder layer.  Every matrix is row-major [out][in] in the configured dtype. */

@@ -32,7 +32,7 @@ class _Config(C.Structure):
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_seq", C.c_int32),
                 ("kv_page", C.c_int32), ("k_cap", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
                 ("ts_alpha0", C.c_double), ("ts_beta0", C.c_double), ("ts_mode", C.c_int32), ("ts_update", C.c_int32),
-                ("gemm_path", C.c_int32), ("tree_width", C.c_int32)]
+                ("gemm_path", C.c_int32), ("tree_width", C.c_int32), ("verify_reuse", C.c_int32), ("reserved", C.c_int32)]
 
 
 class _Calibration(C.Structure):
@@ -191,14 +191,14 @@ class EESD:
 
     def __init__(self, weights: dict, max_seq: int, temperature: float, seed: int = 0, k_cap: int = 10,
                  kv_page: int = 16, alpha0: float = 1.0, beta0: float = 1.0, ts_mode: int = TS_BETA,
-                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0, tree_width: int = 0):
+                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0, tree_width: int = 0, verify_reuse: int = 0):
         sh = weights["shape"]
         self._keep = weights
         self.shape = sh
         self.vocab = sh["vocab"]
         cfg = _Config(sh["n_layers"], sh["n_draft_layers"], sh["d_model"], sh["n_heads"], sh["n_kv_heads"], sh["head_dim"],
                       sh["d_ff"], sh["vocab"], sh["rms_eps"], sh["rope_base"], DTYPE_BF16 if sh["dtype"] == "bf16" else DTYPE_F32,
-                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, tree_width)
+                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, tree_width, verify_reuse, 0)
 
         def lw(d):
             return _Layer(*[d[k].data_ptr() for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])

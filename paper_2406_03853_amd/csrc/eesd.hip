@@ -129,6 +129,7 @@ struct eesd_ctx {
     int64_t cali_n;                       // verifications so far
     float *h_t, *cali_u, *theta_dev;      // H_t^(T) [d], W^i H_t^(T) [d], theta_M
     bf16_t* h_tb;                         // bf16 copy of h_t (operand of the MFMA product)
+    float* hn_rows;                       // verify_reuse: layer-N hidden state of every draft step's input row [k_cap][d]
     int max_splits;
     int row_cap;           // rows the activation buffers hold (16, or PREFILL_ROWS)
     hipEvent_t ev[4];
@@ -596,6 +597,32 @@ static int run_target_rows(eesd_ctx* c, const int32_t* tok_dev, int M, int pos0,
     return EESD_OK;
 }
 
+// The verify block [pending, d_1..d_K] when the K draft steps kept their layer-N hidden states
+// (rows 0..K-1; their keys and values of layers 1..N and of the early-exit layer are in the caches
+// already): layers 1..N and the early-exit K/V for the last draft token alone, then layers N+1..L
+// on all K+1 rows.  Leaves what run_target_rows leaves.
+static int run_target_rows_reusing(eesd_ctx* c, int K, int pos0) {
+    const eesd_config& g = c->cfg;
+    const int d = g.d_model, N = g.n_draft_layers, M = K + 1;
+    const bool mfma1 = pick_mfma(c, 1), mfmaM = pick_mfma(c, M);
+    int rc = launch_embed(c, c->blk_tok + K, 1);
+    if (rc) return rc;
+    if (mfma1 && (rc = launch_rmsnorm_bf16(c, c->x, 1, c->layers[0].attn_norm, c->xb, d))) return rc;
+    for (int l = 0; l < N; ++l) {
+        const void* next_gain = l + 1 < N ? c->layers[l + 1].attn_norm : c->w.ee_layer.attn_norm;
+        if ((rc = run_layer(c, c->layers[l], l, 1, pos0 + K, mfma1, next_gain))) return rc;
+    }
+    if ((rc = run_ee_kv_fill(c, 1, pos0 + K, mfma1))) return rc;
+    hipLaunchKernelGGL(assemble_rows_kernel, dim3((d + 255) / 256), dim3(256), 0, c->stream, c->x, c->hn_rows, K, d);
+    HIP_TRY(c, hipGetLastError());
+    if (mfmaM && (rc = launch_rmsnorm_bf16(c, c->x, M, c->layers[N].attn_norm, c->xb, d))) return rc;
+    for (int l = N; l < g.n_layers; ++l) {
+        const void* next_gain = l + 1 < g.n_layers ? c->layers[l + 1].attn_norm : c->w.final_norm;
+        if ((rc = run_layer(c, c->layers[l], l, M, pos0, mfmaM, next_gain))) return rc;
+    }
+    return EESD_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // paged cache bookkeeping
 // ---------------------------------------------------------------------------------------------
@@ -779,7 +806,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
-                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb};
+                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb, c->hn_rows};
     for (void* p : dev)
         if (p) hipFree(p);
     if (c->h_table) hipHostFree(c->h_table);
@@ -803,6 +830,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if (!(g.temperature >= 0.0f) || !(g.ts_alpha0 > 0.0) || !(g.ts_beta0 > 0.0)) return EESD_EINVAL;
     if (g.ts_mode < 0 || g.ts_mode > 3 || g.ts_update < 0 || g.ts_update > 1 || g.gemm_path < 0 || g.gemm_path > 2) return EESD_EINVAL;
     if (g.tree_width < 0 || g.tree_width > TREE_MAX_WIDTH) return EESD_EINVAL;
+    if (g.verify_reuse < 0 || g.verify_reuse > 1 || g.reserved != 0) return EESD_EINVAL;
     if (g.tree_width >= 2 && (g.temperature != 0.0f || 1 + g.k_cap * g.tree_width > MAX_ROWS)) return EESD_EINVAL;
     const int vec = g.dtype == EESD_DTYPE_BF16 ? 8 : 4;
     const int qd = g.n_heads * g.head_dim;
@@ -841,7 +869,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->xb_has_ssq = false;
     c->xb = c->ab = c->actb = nullptr;
     c->blk_tok = c->prompt_dev = c->result_dev = c->tree_blk = nullptr;
-    c->h_t = c->cali_u = c->theta_dev = nullptr; c->h_tb = nullptr;
+    c->h_t = c->cali_u = c->theta_dev = nullptr; c->h_tb = nullptr; c->hn_rows = nullptr;
     c->cali_set = false; memset(&c->cali, 0, sizeof c->cali);
     c->cali_theta_hat = 0.0; c->cali_weight = 1.0; c->cali_n = 0;
     c->tree_active = false;
@@ -907,6 +935,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if ((rc = dev_alloc(c, &c->cali_u, (size_t)g.d_model))) return bail(rc);
     if ((rc = dev_alloc(c, &c->theta_dev, (size_t)4))) return bail(rc);
     if ((rc = dev_alloc(c, &c->h_tb, (size_t)g.d_model))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->hn_rows, (size_t)g.k_cap * g.d_model))) return bail(rc);
     // rows of the bf16 activation buffers past M are read (and ignored) by the MFMA product
     hipMemset(c->xb, 0, sizeof(bf16_t) * R * d);
     hipMemset(c->ab, 0, sizeof(bf16_t) * R * qd);
@@ -963,6 +992,8 @@ static int save_target_hidden(eesd_ctx* c, int row) {
     HIP_TRY(c, hipGetLastError());
     return EESD_OK;
 }
+
+static bool reuse_hn(const eesd_ctx* c) { return c->cfg.verify_reuse == 1 && c->cfg.tree_width < 2; }
 
 static int tree_width(const eesd_ctx* c) { return c->cfg.tree_width >= 2 ? c->cfg.tree_width : 1; }
 // most rows a verify block can have
@@ -1038,6 +1069,10 @@ extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
         const void* next_gain = l + 1 < g.n_draft_layers ? c->layers[l + 1].attn_norm : c->w.ee_layer.attn_norm;
         if ((rc = run_layer(c, c->layers[l], l, 1, pos, mfma, next_gain))) return rc;
     }
+    if (reuse_hn(c)) {   // this row's layer-N hidden state is what verify would recompute
+        hipLaunchKernelGGL(copy_row_kernel, dim3((g.d_model + 255) / 256), dim3(256), 0, c->stream, c->x, c->hn_rows + (size_t)i * g.d_model, g.d_model);
+        HIP_TRY(c, hipGetLastError());
+    }
     if ((rc = run_layer(c, c->w.ee_layer, g.n_layers, 1, pos, mfma, c->w.ee_norm))) return rc;
     float* ql = c->q_logits + (size_t)i * g.vocab;
     if ((rc = run_head(c, c->w.ee_norm, c->w.ee_head, 0, 1, ql, mfma))) return rc;
@@ -1101,7 +1136,8 @@ extern "C" int eesd_verify(eesd_ctx* c) {
         c->tree_active = true;
         rows_tok = c->tree_blk;
     }
-    rc = run_target_rows(c, rows_tok, M, c->kv_len, mfma);
+    if (reuse_hn(c) && c->n_drafted >= 1) rc = run_target_rows_reusing(c, c->n_drafted, c->kv_len);
+    else rc = run_target_rows(c, rows_tok, M, c->kv_len, mfma);
     c->tree_active = false;
     if (rc) return rc;
     if ((rc = run_head(c, c->w.final_norm, c->w.lm_head, 0, M, c->logits, mfma))) return rc;

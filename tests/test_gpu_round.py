@@ -23,13 +23,16 @@ def _check_caches(o, g, n, tol):
 
 @pytest.mark.parametrize("name", list(SHAPES))
 @pytest.mark.parametrize("temp", [0.0, 1.0])
-def test_teacher_forced_rounds_match_oracle(name, temp):
+@pytest.mark.parametrize("reuse", [0, 1])
+def test_teacher_forced_rounds_match_oracle(name, temp, reuse):
     """Draft logits, verify logits, KV rows and decisions of several rounds, the GPU being fed
-    the oracle's tokens so that one flipped token cannot cascade."""
+    the oracle's tokens so that one flipped token cannot cascade.  reuse = 1: verify takes the
+    layer-N hidden states of the drafted rows from the draft steps (Section 3.1) instead of
+    recomputing them; the oracle always recomputes."""
     require_gpu()
     shape = SHAPES[name]
     tol = tol_of(shape)
-    o, g = make_pair(shape, 3, 128, temp, k_cap=5)
+    o, g = make_pair(shape, 3, 128, temp, k_cap=5, verify_reuse=reuse)
     prompt = si.make_prompt(37, shape["vocab"], 1)      # 2 full blocks of 16 rows + a ragged one
     t_ref = o.prefill(prompt)
     t_gpu = g.prefill(prompt)
@@ -216,6 +219,46 @@ def test_generate_matches_oracle_stream(name, temp, mode):
     assert (st.alpha, st.beta) == (o.ts.alpha, o.ts.beta)
     if gamma is not None:
         assert st.accepted > 5
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_verify_with_reused_hidden_states_equals_full_verify(name):
+    """The same rounds on two contexts, one recomputing layers 1..N for every verify row, one taking
+    them from the draft steps: logits, caches and a greedy generation agree."""
+    require_gpu()
+    import paper_2406_03853_amd as pk
+    shape = SHAPES[name]
+    tol = tol_of(shape)
+    _, g0 = make_pair(shape, 5, 160, 0.0, k_cap=7, gamma=0.05)
+    _, g1 = make_pair(shape, 5, 160, 0.0, k_cap=7, gamma=0.05, verify_reuse=1)
+    prompt = si.make_prompt(20, shape["vocab"], 2)
+    t0 = g0.prefill(prompt)
+    g1.prefill(prompt)
+    g1.force_pending(t0)
+    for K in (7, 1, 4):
+        ds = [g0.draft_step() for _ in range(K)]
+        g1.force_drafts(ds)
+        for _ in range(K):
+            g1.draft_step(sync=False)
+        g0.verify()
+        g1.verify()
+        for i in range(K + 1):
+            assert rel_err(g1.verify_logits(i), g0.verify_logits(i).astype(np.float64)) < 2 * tol, (K, i)
+        a, y = g0.accept()
+        g1.accept()
+        g0.rollback(a)
+        g1.rollback(a)
+        g1.force_pending(y)
+    n = g0.kv_len()
+    for cache in range(shape["n_layers"] + 1):
+        k0, v0 = g0.kv(cache, n)
+        k1, v1 = g1.kv(cache, n)
+        assert rel_err(k1, k0.astype(np.float64)) < 2 * tol and rel_err(v1, v0.astype(np.float64)) < 2 * tol
+    if name == "tiny_fp32":
+        o, g = make_pair(si.TINY, 0, 160, 0.0, k_cap=5, jitter=0.0, gamma=0.05, ts_mode=pk.TS_FIXED, verify_reuse=1)
+        p2 = si.make_prompt(32, 512, 0)
+        spec, st = g.generate(p2, 48)
+        assert spec == o.ar_generate(p2, 48) and st.accepted > 5
 
 
 def test_greedy_speculative_equals_greedy_autoregressive_on_gpu():
