@@ -36,7 +36,16 @@ def pass_bytes(shape, n_layers_run, with_head, kv_tokens, si):
     return b
 
 
-def cpu_baseline(w_gpu, shape, temperature, mean_k, mean_commit, si):
+def oracle_sample_weights(w_gpu, shape, si):
+    """Host copy (fp32 numpy, row-major) of what the CPU baseline runs on: the first 2 layers, the early-exit
+    layer, the heads.  Taken before the GPU copy is rearranged."""
+    sh = si.reduced_depth(shape, 2, 1)
+    sub = dict(shape=sh, tok_emb=w_gpu["tok_emb"], layers=w_gpu["layers"][:2], final_norm=w_gpu["final_norm"],
+               lm_head=w_gpu["lm_head"], ee_layer=w_gpu["ee_layer"], ee_norm=w_gpu["ee_norm"], ee_head=w_gpu["ee_head"])
+    return si.weights_to_numpy(sub)
+
+
+def cpu_baseline(w, shape, temperature, mean_k, mean_commit, si):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample: the same
     weights at depth L=2, N=1, a few rounds; per-parameter time scaled to the full depth."""
     import numpy as np
@@ -46,10 +55,7 @@ def cpu_baseline(w_gpu, shape, temperature, mean_k, mean_commit, si):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    sh = si.reduced_depth(shape, 2, 1)
-    sub = dict(shape=sh, tok_emb=w_gpu["tok_emb"], layers=w_gpu["layers"][:2], final_norm=w_gpu["final_norm"],
-               lm_head=w_gpu["lm_head"], ee_layer=w_gpu["ee_layer"], ee_norm=w_gpu["ee_norm"], ee_head=w_gpu["ee_head"])
-    w = si.weights_to_numpy(sub)
+    sh = w["shape"]
     o = orc.OracleEESD(w, max_seq=64, temperature=temperature, seed=0, k_cap=4)
     o.prefill(si.make_prompt(4, sh["vocab"], 0))
     t_d, t_v, rounds = 0.0, 0.0, 0
@@ -127,6 +133,8 @@ def main():
     ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--tree-width", type=int, default=0,
                     help="2..4: candidate-tree verification (greedy decoding; temperature is set to 0 and K is capped so that 1 + K * width <= 16)")
+    ap.add_argument("--row-major-weights", action="store_true",
+                    help="keep the bf16 matrices row-major instead of the tile-major layout of eesd_pack_weight")
     ap.add_argument("--verify-reuse", action="store_true",
                     help="verify takes the drafted rows' layer-N hidden states from the draft steps instead of recomputing them")
     ap.add_argument("--controller", default="beta", choices=["beta", "cali"],
@@ -163,15 +171,22 @@ def main():
     w = si.make_weights(shape, seed=wseed, device="cuda", correlated_draft=args.draft_correlation)
     torch.cuda.synchronize()
     t_weights = time.perf_counter() - t0
+    cpu_w = None if args.no_cpu_baseline else oracle_sample_weights(w, shape, si)
+    tiled = shape["dtype"] == "bf16" and not args.row_major_weights
+    if tiled:      # one-off rearrangement by the library's own kernel, matrix by matrix
+        w = pk.pack_weights(w)
+        torch.cuda.synchronize()
     max_seq = n_prompt + max_new + k_cap * max(1, args.tree_width) + 2
     sweep_tokens = 2048 if args.workload == "70b" else n_prompt       # cache length of the latency sweep
     if args.latency_sweep:
         max_seq = max(max_seq, sweep_tokens + k_cap + 2)
     max_seq = (max_seq + 63) // 64 * 64
     ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64, tree_width=args.tree_width, verify_reuse=int(args.verify_reuse),
+                  weight_layout=pk.WEIGHTS_TILED if tiled else pk.WEIGHTS_ROW_MAJOR,
                   ts_mode=pk.TS_CALI if args.controller == "cali" else pk.TS_BETA)
     if args.controller == "cali":
-        ctx.set_calibration(si.make_cali_weights(shape, wseed, device="cuda"), 0.2, 0.5, 0.5)
+        cw = si.make_cali_weights(shape, wseed, device="cuda")
+        ctx.set_calibration(pk.pack_calibration(cw) if tiled else cw, 0.2, 0.5, 0.5)
     # one prompt per step: with random weights the acceptance of a single stream is a matter of luck
     # (14-21 % here), so the steps run different streams and the rate is their mean
     prompts = [si.make_prompt(n_prompt, shape["vocab"], i) for i in range(max(1, args.steps))]
@@ -228,6 +243,7 @@ def main():
                                f"prompt {n_prompt} uniform ids (a different one per step), {max_new} new tokens, Beta-TS K cap {k_cap}, "
                                f"temperature {args.temperature:g}, batch 1"
                                + (f", candidate tree of width {args.tree_width}" if args.tree_width >= 2 else "")
+                               + (", tile-major weight layout" if tiled else ", row-major weights")
                                + (", verify reuses the draft steps' layer-N hidden states" if args.verify_reuse else "")
                                + (", calibrated controller with a random predictor" if args.controller == "cali" else "")
                                + (f", draft correlated with the target (gamma {args.draft_correlation:g})" if args.draft_correlation is not None else ""),
@@ -256,7 +272,7 @@ def main():
     if args.latency_sweep:
         out["latency_vs_K"] = latency_sweep(ctx, torch, sweep_tokens, k_cap, b_draft, shape, si)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, shape, args.temperature, mean_k, mean_commit, si)
+        out["cpu_baseline"] = cpu_baseline(cpu_w, shape, args.temperature, mean_k, mean_commit, si)
     print(json.dumps(out))
 
 

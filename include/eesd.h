@@ -47,6 +47,8 @@ typedef enum eesd_status {
 } eesd_status;
 
 enum { EESD_DTYPE_F32 = 0, EESD_DTYPE_BF16 = 1 };
+enum { EESD_WEIGHTS_ROW_MAJOR = 0, EESD_WEIGHTS_TILED = 1 };
+enum { EESD_PACK_PLAIN = 0, EESD_PACK_GATE_UP = 1, EESD_PACK_QKV = 2 };
 enum { EESD_TS_BETA = 0, EESD_TS_FIXED = 1, EESD_TS_SCHEDULE = 2, EESD_TS_CALI = 3 };
 enum { EESD_GEMM_AUTO = 0, EESD_GEMM_VALU = 1, EESD_GEMM_MFMA = 2 };
 
@@ -85,7 +87,8 @@ typedef struct eesd_config {
                                 computed them (Section 3.1: the draft model IS the target's first N layers) and runs
                                 layers 1..N for the last draft token only; 0: all L layers on all K+1 rows.  Same
                                 result up to rounding; ignored in tree mode */
-    int32_t reserved;        /* 0 */
+    int32_t weight_layout;   /* EESD_WEIGHTS_ROW_MAJOR, or EESD_WEIGHTS_TILED: every matrix except tok_emb and the norm gains
+                                was rearranged by eesd_pack_weight (bf16 models, MFMA kernel family only) */
 } eesd_config;
 
 /* One decoder layer.  Every matrix is row-major [out][in] in the configured dtype. */
@@ -216,7 +219,8 @@ int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t
 /* The predictor of Eq. 5 and the hyper-parameters of the Gaussian posterior.  w and wp are DEVICE
  * pointers, BORROWED until eesd_destroy, row-major [out][in] in the model's storage type. */
 typedef struct eesd_calibration {
-    const void* w;       /* W^1..W^n_mats: [n_mats][d_model][d_model]; draft step i uses W^min(i, n_mats) */
+    const void* w;       /* W^1..W^n_mats: [n_mats][d_model][d_model]; draft step i uses W^min(i, n_mats).  Each matrix
+                            in the context's weight_layout (EESD_PACK_PLAIN) */
     const void* wp;      /* W_p: [2][2 d_model]; its input is (W^i H_t^(T), H_{t+i}^(D)) */
     int32_t n_mats;      /* 1..10 */
     int32_t update;      /* reading of Eq. 8: 0: theta_hat is the mean of the chi the target judged (a successes out of
@@ -298,10 +302,22 @@ int eesd_op_softmax_sample(const float* logits, float* probs, int32_t vocab, flo
                            void* hip_stream, int32_t* token);
 /* Y[m][r] = sum_k X[m][k] W[r][k]: the weight-streaming product of the draft (M = 1), verify
  * (M = K+1 <= 16) and prefill (M <= 128, bf16 MFMA family, out % 64 == 0, in % 256 == 0) passes
- * without prologue or epilogue.  W: DEVICE [out][in] in dtype; X: DEVICE fp32 [M][in];
- * Y: DEVICE fp32 [M][out]; path: EESD_GEMM_*. */
+ * without prologue or epilogue.  W: DEVICE [out][in] in dtype (weight_layout EESD_WEIGHTS_TILED:
+ * packed with kind EESD_PACK_PLAIN); X: DEVICE fp32 [M][in]; Y: DEVICE fp32 [M][out]; path: EESD_GEMM_*. */
 int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,
-                 int32_t dtype, int32_t path, void* hip_stream);
+                 int32_t dtype, int32_t path, int32_t weight_layout, void* hip_stream);
+
+/* Rearranges one bf16 weight matrix (DEVICE, row-major [out_rows][in_dim]) into the tile-major layout
+ * the MFMA kernel family reads with one contiguous 1 KB access per operand (EESD_WEIGHTS_TILED):
+ * tiles of 16 rows, each stored as in_dim/32 blocks of 1 KB, a block holding 32 columns of the 16
+ * rows in the lane order of the MFMA operand.  Which 16 rows form a tile follows the epilogue the
+ * matrix feeds: kind EESD_PACK_PLAIN (LM heads, attention output, FFN down, the calibration
+ * matrices): 16 consecutive rows; EESD_PACK_GATE_UP (fused gate|up, out_rows = 2 d_ff): 8 gate rows
+ * and their 8 up rows; EESD_PACK_QKV (fused q|k|v; head_dim given): 8 rows of a head and their
+ * rotary partners head_dim/2 further.  dst: DEVICE, out_rows * in_dim elements, must not overlap
+ * src.  out_rows % 16 == 0 (QKV: % head_dim), in_dim % 128 == 0.  Does not synchronise. */
+int eesd_pack_weight(const void* src, void* dst, int32_t out_rows, int32_t in_dim, int32_t kind, int32_t head_dim,
+                     void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -14,6 +14,8 @@ import numpy as np
 
 DTYPE_F32, DTYPE_BF16 = 0, 1
 TS_BETA, TS_FIXED, TS_SCHEDULE, TS_CALI = 0, 1, 2, 3
+WEIGHTS_ROW_MAJOR, WEIGHTS_TILED = 0, 1
+PACK_PLAIN, PACK_GATE_UP, PACK_QKV = 0, 1, 2
 GEMM_AUTO, GEMM_VALU, GEMM_MFMA = 0, 1, 2
 READ_DRAFT_LOGITS, READ_DRAFT_PROBS, READ_VERIFY_LOGITS, READ_KV_K, READ_KV_V, READ_TOKENS, READ_KV_LEN, READ_PAGE_TABLE, READ_TREE_TOKENS, READ_CALI_STATE = range(10)
 
@@ -32,7 +34,7 @@ class _Config(C.Structure):
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_seq", C.c_int32),
                 ("kv_page", C.c_int32), ("k_cap", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
                 ("ts_alpha0", C.c_double), ("ts_beta0", C.c_double), ("ts_mode", C.c_int32), ("ts_update", C.c_int32),
-                ("gemm_path", C.c_int32), ("tree_width", C.c_int32), ("verify_reuse", C.c_int32), ("reserved", C.c_int32)]
+                ("gemm_path", C.c_int32), ("tree_width", C.c_int32), ("verify_reuse", C.c_int32), ("weight_layout", C.c_int32)]
 
 
 class _Calibration(C.Structure):
@@ -81,7 +83,7 @@ EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "ee
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
            "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_set_calibration", "eesd_cali_score",
-           "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm"]
+           "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm", "eesd_pack_weight"]
 
 
 def lib() -> C.CDLL:
@@ -128,7 +130,8 @@ def lib() -> C.CDLL:
     L.eesd_host_cali_update.argtypes = [P(C.c_double), P(C.c_double), P(C.c_int64), I32, I32, I32]
     L.eesd_op_accept.argtypes = [VP, VP, VP, P(C.c_double), I32, I32, I32, VP, P(I32)]
     L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
-    L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, VP]
+    L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, I32, VP]
+    L.eesd_pack_weight.argtypes = [VP, VP, I32, I32, I32, I32, VP]
     for name in EXPORTS:
         if name not in ("eesd_destroy", "eesd_last_error", "eesd_host_uniform"):
             getattr(L, name).restype = C.c_int
@@ -191,14 +194,14 @@ class EESD:
 
     def __init__(self, weights: dict, max_seq: int, temperature: float, seed: int = 0, k_cap: int = 10,
                  kv_page: int = 16, alpha0: float = 1.0, beta0: float = 1.0, ts_mode: int = TS_BETA,
-                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0, tree_width: int = 0, verify_reuse: int = 0):
+                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0, tree_width: int = 0, verify_reuse: int = 0, weight_layout: int = WEIGHTS_ROW_MAJOR):
         sh = weights["shape"]
         self._keep = weights
         self.shape = sh
         self.vocab = sh["vocab"]
         cfg = _Config(sh["n_layers"], sh["n_draft_layers"], sh["d_model"], sh["n_heads"], sh["n_kv_heads"], sh["head_dim"],
                       sh["d_ff"], sh["vocab"], sh["rms_eps"], sh["rope_base"], DTYPE_BF16 if sh["dtype"] == "bf16" else DTYPE_F32,
-                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, tree_width, verify_reuse, 0)
+                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, tree_width, verify_reuse, weight_layout)
 
         def lw(d):
             return _Layer(*[d[k].data_ptr() for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
@@ -378,11 +381,50 @@ def calibration_copy(dst, src, stream: int = 0) -> None:
         raise EesdError(rc, "eesd_debug_copy")
 
 
-def op_gemm(W, X, Y, path: int = GEMM_AUTO, stream: int = 0) -> None:
+def op_gemm(W, X, Y, path: int = GEMM_AUTO, stream: int = 0, weight_layout: int = WEIGHTS_ROW_MAJOR) -> None:
     import torch
     M, inn = X.shape
     out = W.shape[0]
     dt = DTYPE_BF16 if W.dtype == torch.bfloat16 else DTYPE_F32
-    rc = lib().eesd_op_gemm(W.data_ptr(), X.data_ptr(), Y.data_ptr(), M, out, inn, dt, path, C.c_void_p(stream))
+    rc = lib().eesd_op_gemm(W.data_ptr(), X.data_ptr(), Y.data_ptr(), M, out, inn, dt, path, weight_layout, C.c_void_p(stream))
     if rc:
         raise EesdError(rc, "eesd_op_gemm")
+
+
+def pack_weight(W, kind: int = PACK_PLAIN, head_dim: int = 0, stream: int = 0):
+    """Tile-major copy of one bf16 matrix [out][in] (same shape and dtype; the library's kernel does the
+    rearranging, torch only owns the new buffer)."""
+    import torch
+    assert W.dtype == torch.bfloat16 and W.is_contiguous() and W.dim() == 2
+    dst = torch.empty_like(W)
+    rc = lib().eesd_pack_weight(W.data_ptr(), dst.data_ptr(), W.shape[0], W.shape[1], kind, head_dim, C.c_void_p(stream))
+    if rc:
+        raise EesdError(rc, "eesd_pack_weight")
+    return dst
+
+
+def pack_weights(weights: dict) -> dict:
+    """All matrices of a model dict in the tile-major layout (EESD(..., weight_layout=WEIGHTS_TILED)).
+    Matrix by matrix, dropping this function's reference to each original as it goes, so a caller who
+    gives up its own dict needs room for the model plus one matrix."""
+    hd = weights["shape"]["head_dim"]
+    out = dict(shape=dict(weights["shape"]), tok_emb=weights["tok_emb"], final_norm=weights["final_norm"], ee_norm=weights["ee_norm"])
+
+    def layer(l):
+        return dict(attn_norm=l["attn_norm"], ffn_norm=l["ffn_norm"], wqkv=pack_weight(l["wqkv"], PACK_QKV, hd), wo=pack_weight(l["wo"]),
+                    w_gate_up=pack_weight(l["w_gate_up"], PACK_GATE_UP), w_down=pack_weight(l["w_down"]))
+    out["layers"] = []
+    layers = weights["layers"]
+    for i in range(len(layers)):
+        out["layers"].append(layer(layers[i]))
+        layers[i] = None          # the caller's list gives the original up as well
+    weights["layers"] = []
+    out["ee_layer"] = layer(weights.pop("ee_layer"))
+    out["lm_head"] = pack_weight(weights.pop("lm_head"))
+    out["ee_head"] = pack_weight(weights.pop("ee_head"))
+    return out
+
+
+def pack_calibration(cw: dict) -> dict:
+    import torch
+    return dict(w=torch.stack([pack_weight(cw["w"][i].contiguous()) for i in range(cw["w"].shape[0])]), wp=cw["wp"])

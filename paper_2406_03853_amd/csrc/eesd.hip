@@ -315,7 +315,7 @@ static bool mfma_shape_ok(int out, int in, int epi, int head_dim) {
 static bool pick_mfma(const eesd_ctx* c, int M) {
     if (!is_bf16(c)) return false;
     if (c->cfg.gemm_path == EESD_GEMM_VALU) return false;
-    if (c->cfg.gemm_path == EESD_GEMM_MFMA) return true;
+    if (c->cfg.gemm_path == EESD_GEMM_MFMA || c->cfg.weight_layout == EESD_WEIGHTS_TILED) return true;
     return M >= g_mfma_min_m;
 }
 
@@ -333,7 +333,13 @@ static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
         }
         HIP_TRY(c, hipEventRecord(c->prof_ev[2 * c->prof_used], c->stream));
     }
-    HIP_TRY(c, mfma ? launch_mfma<EPI>(p, ksplit, c->stream) : launch_valu<EPI>(p, is_bf16(c), c->stream));
+    if (mfma) {
+        GemmP pm = p;
+        pm.w_packed = c->cfg.weight_layout == EESD_WEIGHTS_TILED;
+        HIP_TRY(c, launch_mfma<EPI>(pm, ksplit, c->stream));
+    } else {
+        HIP_TRY(c, launch_valu<EPI>(p, is_bf16(c), c->stream));
+    }
     if (prof) {
         HIP_TRY(c, hipEventRecord(c->prof_ev[2 * c->prof_used + 1], c->stream));
         ++c->prof_used;
@@ -830,7 +836,9 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if (!(g.temperature >= 0.0f) || !(g.ts_alpha0 > 0.0) || !(g.ts_beta0 > 0.0)) return EESD_EINVAL;
     if (g.ts_mode < 0 || g.ts_mode > 3 || g.ts_update < 0 || g.ts_update > 1 || g.gemm_path < 0 || g.gemm_path > 2) return EESD_EINVAL;
     if (g.tree_width < 0 || g.tree_width > TREE_MAX_WIDTH) return EESD_EINVAL;
-    if (g.verify_reuse < 0 || g.verify_reuse > 1 || g.reserved != 0) return EESD_EINVAL;
+    if (g.verify_reuse < 0 || g.verify_reuse > 1) return EESD_EINVAL;
+    if (g.weight_layout != EESD_WEIGHTS_ROW_MAJOR && g.weight_layout != EESD_WEIGHTS_TILED) return EESD_EINVAL;
+    if (g.weight_layout == EESD_WEIGHTS_TILED && (g.dtype != EESD_DTYPE_BF16 || g.gemm_path == EESD_GEMM_VALU)) return EESD_EINVAL;
     if (g.tree_width >= 2 && (g.temperature != 0.0f || 1 + g.k_cap * g.tree_width > MAX_ROWS)) return EESD_EINVAL;
     const int vec = g.dtype == EESD_DTYPE_BF16 ? 8 : 4;
     const int qd = g.n_heads * g.head_dim;
@@ -1583,13 +1591,29 @@ extern "C" int eesd_op_softmax_sample(const float* logits, float* probs, int32_t
     return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
 }
 
+extern "C" int eesd_pack_weight(const void* src, void* dst, int32_t out_rows, int32_t in_dim, int32_t kind, int32_t head_dim, void* hip_stream) {
+    if (!src || !dst || src == dst || out_rows < 16 || in_dim < 32 || in_dim % 32) return EESD_EINVAL;
+    int epi;
+    if (kind == EESD_PACK_PLAIN) epi = EPI_PLAIN;
+    else if (kind == EESD_PACK_GATE_UP) epi = EPI_SWIGLU;
+    else if (kind == EESD_PACK_QKV) epi = EPI_QKV;
+    else return EESD_EINVAL;
+    if (!mfma_shape_ok(out_rows, in_dim, epi, head_dim)) return EESD_EINVAL;
+    const long long pieces = (long long)out_rows * in_dim / 8;
+    hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream, (const bf16_t*)src,
+                       (bf16_t*)dst, out_rows, in_dim, epi, head_dim);
+    return hipGetLastError() == hipSuccess ? EESD_OK : EESD_EDEVICE;
+}
+
 extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in, int32_t dtype, int32_t path,
-                            void* hip_stream) {
+                            int32_t weight_layout, void* hip_stream) {
     if (!W || !X || !Y || M < 1 || M > PREFILL_ROWS || out < 2 || in < 8) return EESD_EINVAL;
+    if (weight_layout != EESD_WEIGHTS_ROW_MAJOR && weight_layout != EESD_WEIGHTS_TILED) return EESD_EINVAL;
+    if (weight_layout == EESD_WEIGHTS_TILED && (dtype != EESD_DTYPE_BF16 || path == EESD_GEMM_VALU)) return EESD_EINVAL;
     if (dtype != EESD_DTYPE_F32 && dtype != EESD_DTYPE_BF16) return EESD_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     const bool b16 = dtype == EESD_DTYPE_BF16;
-    bool mfma = b16 && (path == EESD_GEMM_MFMA || (path == EESD_GEMM_AUTO && M >= g_mfma_min_m));
+    bool mfma = b16 && (path == EESD_GEMM_MFMA || weight_layout == EESD_WEIGHTS_TILED || (path == EESD_GEMM_AUTO && M >= g_mfma_min_m));
     if (path == EESD_GEMM_MFMA && !b16) return EESD_EINVAL;
     if (mfma) {
         if (!mfma_shape_ok(out, in, EPI_PLAIN, 0)) return EESD_EINVAL;
@@ -1611,6 +1635,7 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
         if (e == hipSuccess) {
             GemmP p = gemm_base(W, xb, in, M, out, in);
             p.Y = Y; p.ldy = out;
+            p.w_packed = weight_layout == EESD_WEIGHTS_TILED;
             e = launch_mfma<EPI_PLAIN>(p, 1, st);
         }
         return e == hipSuccess ? EESD_OK : EESD_EDEVICE;

@@ -34,7 +34,10 @@ def make_pair(shape, wseed, max_seq, temperature, k_cap=5, jitter=0.1, gamma=Non
     else:
         o = orc.OracleEESD(si.weights_to_numpy(w), max_seq, temperature, seed=kw.get("seed", 0), k_cap=k_cap,
                            ts_update="literal" if kw.get("ts_update", 0) else "prose")
-    g = pk.EESD(si.weights_to_device(w, "cuda"), max_seq, temperature, k_cap=k_cap, **kw)
+    wd = si.weights_to_device(w, "cuda")
+    if kw.get("weight_layout", 0) == pk.WEIGHTS_TILED:
+        wd = pk.pack_weights(wd)
+    g = pk.EESD(wd, max_seq, temperature, k_cap=k_cap, **kw)
     return o, g
 
 

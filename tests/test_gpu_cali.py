@@ -18,14 +18,17 @@ def _cali_pair(shape, seed, device="cuda"):
     return si.cali_to_numpy(cw), {k: v.to(device).contiguous() for k, v in cw.items()}
 
 
-@pytest.mark.parametrize("name", list(SHAPES))
+@pytest.mark.parametrize("name,tiled", [("tiny_fp32", 0), ("gqa_bf16", 0), ("gqa_bf16", 1)])
 @pytest.mark.parametrize("temp", [0.0, 1.0])
-def test_predictor_scores_match_oracle_under_teacher_forcing(name, temp):
+def test_predictor_scores_match_oracle_under_teacher_forcing(name, temp, tiled):
     require_gpu()
+    import paper_2406_03853_amd as pk
     shape = SHAPES[name]
     tol = tol_of(shape)
-    o, g = make_pair(shape, 3, 160, temp, k_cap=12, gamma=0.05)
+    o, g = make_pair(shape, 3, 160, temp, k_cap=12, gamma=0.05, weight_layout=tiled)
     cw_np, cw_gpu = _cali_pair(shape, 1)
+    if tiled:
+        cw_gpu = pk.pack_calibration(cw_gpu)
     g.set_calibration(cw_gpu, 0.2, 0.5, 0.5)
     cali = orc.CaliTS(0.2, 0.5, 0.5)
     prompt = si.make_prompt(21, shape["vocab"], 1)

@@ -36,12 +36,13 @@ def _round_parity(o, g, ks, tol):
         g.force_pending(y)
 
 
-@pytest.mark.parametrize("name,n_prompt,ks", [("13b", 150, (10, 3)), ("70b", 40, (7,))])
-def test_full_width_reduced_depth_matches_oracle(name, n_prompt, ks):
+@pytest.mark.parametrize("name,n_prompt,ks,tiled", [("13b", 150, (10, 3), 0), ("70b", 40, (7,), 0), ("13b", 150, (10, 3), 1), ("70b", 140, (7, 2), 1)])
+def test_full_width_reduced_depth_matches_oracle(name, n_prompt, ks, tiled):
+    """tiled = 1: the weights in the tile-major layout the benchmark runs with."""
     require_gpu()
     base = si.LLAMA13B if name == "13b" else si.LLAMA70B
     shape = si.reduced_depth(base, 2, 1)
-    o, g = make_pair(shape, 21, n_prompt + 64, 1.0, k_cap=10, jitter=0.05, gen_device="cuda", kv_page=64)
+    o, g = make_pair(shape, 21, n_prompt + 64, 1.0, k_cap=10, jitter=0.05, gen_device="cuda", kv_page=64, weight_layout=tiled)
     prompt = si.make_prompt(n_prompt, shape["vocab"], 3)
     t_ref = o.prefill(prompt)          # 128-row tiled block + ragged block on the GPU side
     g.prefill(prompt)
@@ -94,9 +95,9 @@ def test_full_depth_70b_properties():
     require_gpu()
     import paper_2406_03853_amd as pk
     shape = si.LLAMA70B
-    w = si.make_weights(shape, seed=2, device="cuda")
-    g1 = pk.EESD(w, max_seq=2176, temperature=0.0, k_cap=10, kv_page=64)
-    g2 = pk.EESD(w, max_seq=2176, temperature=0.0, k_cap=10, kv_page=64)
+    w = pk.pack_weights(si.make_weights(shape, seed=2, device="cuda"))      # as the benchmark runs: tile-major weights
+    g1 = pk.EESD(w, max_seq=2176, temperature=0.0, k_cap=10, kv_page=64, weight_layout=pk.WEIGHTS_TILED)
+    g2 = pk.EESD(w, max_seq=2176, temperature=0.0, k_cap=10, kv_page=64, weight_layout=pk.WEIGHTS_TILED)
     prompt = si.make_prompt(2048, shape["vocab"], 4)
     block = [int(t) for t in si.make_prompt(5, shape["vocab"], 5)]
     for g in (g1, g2):

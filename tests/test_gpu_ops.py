@@ -91,6 +91,57 @@ def test_gemm_tile_kernel_prefill_chunk_256(M):
         pk.set_tunable("pf_kc", 0)
 
 
+@pytest.mark.parametrize("M", [1, 5, 11, 16, 40, 128])
+@pytest.mark.parametrize("out,inn", [(1024, 512), (5120, 5120), (320, 13824), (32000, 1024), (64, 256)])
+def test_gemm_tiled_weight_layout_equals_row_major(M, out, inn):
+    """The tile-major weight layout (one contiguous 1 KB read per MFMA operand): the same product,
+    bit for bit, as from the row-major matrix - the loads change, the arithmetic does not."""
+    require_gpu()
+    pk = _pk()
+    g = torch.Generator(device="cpu").manual_seed(out + inn + M)
+    W = (torch.randn(out, inn, generator=g) * 0.05).to(torch.bfloat16).cuda()
+    X = torch.randn(M, inn, generator=g).cuda()
+    Y0 = torch.empty(M, out, device="cuda")
+    Y1 = torch.empty(M, out, device="cuda")
+    Wp = pk.pack_weight(W)
+    assert Wp.shape == W.shape and not torch.equal(Wp, W)
+    for tile in (0, 1):
+        try:
+            pk.set_tunable("mfma_tile", tile)
+            pk.op_gemm(W, X, Y0, pk.GEMM_MFMA)
+            pk.op_gemm(Wp, X, Y1, pk.GEMM_MFMA, weight_layout=pk.WEIGHTS_TILED)
+            torch.cuda.synchronize()
+            assert torch.equal(Y0, Y1)
+        finally:
+            pk.set_tunable("mfma_tile", 0)
+    ref = X.double().cpu().numpy() @ W.double().cpu().numpy().T
+    assert np.max(np.abs(Y1.cpu().numpy() - ref)) / np.max(np.abs(ref)) < TOL_BF16
+
+
+def test_pack_weight_is_a_permutation_of_16_byte_pieces():
+    require_gpu()
+    pk = _pk()
+    out, inn, hd = 512, 256, 128
+    W = torch.arange(out * inn, dtype=torch.float32).remainder(65521).to(torch.bfloat16).reshape(out, inn).cuda()
+    for kind, hdim in ((pk.PACK_PLAIN, 0), (pk.PACK_GATE_UP, 0), (pk.PACK_QKV, hd)):
+        P = pk.pack_weight(W, kind, hdim).cpu().view(torch.int16).numpy().reshape(out // 16, inn // 32, 4, 16, 8)   # [tile][q][g][i][8]
+        Wn = W.cpu().view(torch.int16).numpy()
+        for tile in (0, 1, out // 16 - 1):
+            for i in (0, 7, 8, 15):
+                if kind == pk.PACK_PLAIN:
+                    row = tile * 16 + i
+                elif kind == pk.PACK_GATE_UP:
+                    row = (0 if i < 8 else out // 2) + tile * 8 + (i & 7)
+                else:
+                    head, part = divmod(tile, hd // 16)
+                    row = head * hd + (0 if i < 8 else hd // 2) + part * 8 + (i & 7)
+                for q in (0, inn // 32 - 1):
+                    for g in range(4):
+                        assert (P[tile, q, g, i] == Wn[row, q * 32 + g * 8: q * 32 + g * 8 + 8]).all(), (kind, tile, i, q, g)
+    with pytest.raises(pk.EesdError):
+        pk.pack_weight(W[:, :96].contiguous())        # columns not a multiple of 128
+
+
 @pytest.mark.parametrize("nw", [1, 2, 4, 16])
 def test_gemm_mfma_launch_shapes(nw):
     require_gpu()

@@ -221,6 +221,27 @@ def test_generate_matches_oracle_stream(name, temp, mode):
         assert st.accepted > 5
 
 
+@pytest.mark.parametrize("temp,tree", [(1.0, 0), (0.0, 0), (0.0, 2)])
+def test_tiled_weight_layout_generates_the_same_tokens(temp, tree):
+    """Whole generations (prefill blocks, draft steps, verify blocks of every size, all epilogues) from
+    tile-major weights equal those from the row-major weights: the layout changes loads only."""
+    require_gpu()
+    import paper_2406_03853_amd as pk
+    shape = SHAPES["gqa_bf16"]
+    kw = dict(k_cap=6, gamma=0.05, ts_mode=pk.TS_FIXED, tree_width=tree)
+    _, g0 = make_pair(shape, 13, 400, temp, **kw)
+    _, g1 = make_pair(shape, 13, 400, temp, weight_layout=pk.WEIGHTS_TILED, **kw)
+    prompt = si.make_prompt(150, shape["vocab"], 3)        # a 128-row prefill block and a ragged one
+    a, sa = g0.generate(prompt, 60)
+    b, sb = g1.generate(prompt, 60)
+    assert a == b and (sa.rounds, sa.accepted) == (sb.rounds, sb.accepted)
+    assert np.array_equal(g0.verify_logits(0), g1.verify_logits(0))
+    with pytest.raises(pk.EesdError):
+        pk.EESD(si.weights_to_device(si.make_weights(shape, seed=1), "cuda"), 64, 1.0, weight_layout=pk.WEIGHTS_TILED, gemm_path=pk.GEMM_VALU)
+    with pytest.raises(pk.EesdError):
+        pk.EESD(si.weights_to_device(si.make_weights(si.TINY, seed=1), "cuda"), 64, 1.0, weight_layout=pk.WEIGHTS_TILED)
+
+
 @pytest.mark.parametrize("name", list(SHAPES))
 def test_verify_with_reused_hidden_states_equals_full_verify(name):
     """The same rounds on two contexts, one recomputing layers 1..N for every verify row, one taking
