@@ -39,6 +39,7 @@ static int g_attn_split = 0;   // keys per attention split
 static int g_tile_kc = 0;      // 512: the tile kernel takes 512-column chunks for verify-sized blocks (default 256)
 static int g_tile_nwt = 0;     // 4 / 8: tiles per workgroup of the tile kernel for verify-sized blocks (0 = by tile count)
 static int g_fuse_norm = -1;   // residual -> next product hand-over without resid_norm_kernel: 1 on, 0 off, -1 by model width
+static int g_nw_epi[4] = {0, 0, 0, 0};   // waves per workgroup of the per-tile product by epilogue (plain, resid, swiglu, qkv)
 static int g_pf_kc = 0;        // 256: prefill blocks take 256-column chunks (default 128)
 static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: by rows and tile count
 static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
@@ -47,7 +48,7 @@ extern "C" int eesd_set_tunable(const char* name, int value) {
     if (!name) return EESD_EINVAL;
     struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
                                              {"mfma_ksplit", &g_mfma_ksplit}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
-                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
+                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
     for (auto& e : t)
         if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
     return EESD_EINVAL;
@@ -284,7 +285,7 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
     }
     if (p.M > 16) return hipErrorInvalidValue;
     const int n_tiles = p.out_rows / 16, steps = p.in_dim / 128;
-    int nw = g_mfma_nw;
+    int nw = g_nw_epi[EPI] ? g_nw_epi[EPI] : g_mfma_nw;
     if (!nw) {
         if (EPI == EPI_RESID && p.y_partial) {
             // K is already split over workgroups: 2-4 waves each, at least two 128-column steps per wave
@@ -295,6 +296,12 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
             // one workgroup per tile: many waves per tile keep the tail short when tiles / CU is
             // small or fractional (measured best at 8 for the QKV, gate/up and head products)
             nw = 8;
+            // tile-major weights at the 70B shape: every wave access is a contiguous KB, and fewer,
+            // longer waves stream better - 2 for the widest product (3584 tiles), 4 for the residual
+            // products that keep K whole (measured together: 293 instead of 304 us per layer; at the
+            // 13B shape 8 stays best everywhere)
+            if (p.w_packed && EPI == EPI_SWIGLU && n_tiles >= 3072) nw = 2;
+            if (p.w_packed && EPI == EPI_RESID && p.xb_out) nw = 4;
             while (nw > 1 && steps / nw < 4) nw >>= 1;
         }
     }
