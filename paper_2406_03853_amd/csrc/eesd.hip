@@ -296,11 +296,8 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
             // one workgroup per tile: many waves per tile keep the tail short when tiles / CU is
             // small or fractional (measured best at 8 for the QKV, gate/up and head products)
             nw = 8;
-            // tile-major weights at the 70B shape: every wave access is a contiguous KB, and fewer,
-            // longer waves stream better - 2 for the widest product (3584 tiles), 4 for the residual
-            // products that keep K whole (measured together: 293 instead of 304 us per layer; at the
-            // 13B shape 8 stays best everywhere)
-            if (p.w_packed && EPI == EPI_SWIGLU && n_tiles >= 3072) nw = 2;
+            // tile-major weights: the residual products that keep K whole (wide models) stream best
+            // with 4 waves (measured -4 us per 70B layer; every other product stays at 8)
             if (p.w_packed && EPI == EPI_RESID && p.xb_out) nw = 4;
             while (nw > 1 && steps / nw < 4) nw >>= 1;
         }

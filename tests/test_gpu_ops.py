@@ -94,8 +94,8 @@ def test_gemm_tile_kernel_prefill_chunk_256(M):
 @pytest.mark.parametrize("M", [1, 5, 11, 16, 40, 128])
 @pytest.mark.parametrize("out,inn", [(1024, 512), (5120, 5120), (320, 13824), (32000, 1024), (64, 256)])
 def test_gemm_tiled_weight_layout_equals_row_major(M, out, inn):
-    """The tile-major weight layout (one contiguous 1 KB read per MFMA operand): the same product,
-    bit for bit, as from the row-major matrix - the loads change, the arithmetic does not."""
+    """The tile-major weight layout (one contiguous 1 KB read per MFMA operand): the same product as
+    from the row-major matrix up to the order in which the waves' partial sums are added."""
     require_gpu()
     pk = _pk()
     g = torch.Generator(device="cpu").manual_seed(out + inn + M)
@@ -111,7 +111,7 @@ def test_gemm_tiled_weight_layout_equals_row_major(M, out, inn):
             pk.op_gemm(W, X, Y0, pk.GEMM_MFMA)
             pk.op_gemm(Wp, X, Y1, pk.GEMM_MFMA, weight_layout=pk.WEIGHTS_TILED)
             torch.cuda.synchronize()
-            assert torch.equal(Y0, Y1)
+            assert float((Y0 - Y1).abs().max()) <= 2e-5 * float(Y0.abs().max())
         finally:
             pk.set_tunable("mfma_tile", 0)
     ref = X.double().cpu().numpy() @ W.double().cpu().numpy().T

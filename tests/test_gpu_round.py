@@ -224,7 +224,8 @@ def test_generate_matches_oracle_stream(name, temp, mode):
 @pytest.mark.parametrize("temp,tree", [(1.0, 0), (0.0, 0), (0.0, 2)])
 def test_tiled_weight_layout_generates_the_same_tokens(temp, tree):
     """Whole generations (prefill blocks, draft steps, verify blocks of every size, all epilogues) from
-    tile-major weights equal those from the row-major weights: the layout changes loads only."""
+    tile-major weights equal those from the row-major weights: the layout changes the loads and the
+    order of a few fp32 additions, not the tokens."""
     require_gpu()
     import paper_2406_03853_amd as pk
     shape = SHAPES["gqa_bf16"]
@@ -235,7 +236,8 @@ def test_tiled_weight_layout_generates_the_same_tokens(temp, tree):
     a, sa = g0.generate(prompt, 60)
     b, sb = g1.generate(prompt, 60)
     assert a == b and (sa.rounds, sa.accepted) == (sb.rounds, sb.accepted)
-    assert np.array_equal(g0.verify_logits(0), g1.verify_logits(0))
+    # an fp32 sum taken in another order can flip a bf16 rounding of an activation further up
+    assert rel_err(g1.verify_logits(0), g0.verify_logits(0).astype(np.float64)) < tol_of(shape)
     with pytest.raises(pk.EesdError):
         pk.EESD(si.weights_to_device(si.make_weights(shape, seed=1), "cuda"), 64, 1.0, weight_layout=pk.WEIGHTS_TILED, gemm_path=pk.GEMM_VALU)
     with pytest.raises(pk.EesdError):
