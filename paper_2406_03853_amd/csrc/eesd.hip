@@ -267,7 +267,10 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
     const bool partial = EPI == EPI_RESID && p.y_partial;
     bool use_tile = p.M > 16;
     if (p.M <= 16 && g_mfma_tile == 1) use_tile = true;
-    if (p.M <= 16 && g_mfma_tile == 0) use_tile = p.M >= (n_tiles16 >= 3072 ? 7 : 6) && n_tiles16 >= 1536 && !partial;
+    // crossover rows (measured): row-major weights 6, 7 for the widest products; tile-major weights, whose
+    // per-tile kernel leaves the activation rows in L2, 7 and 10
+    const int tile_min_m = p.w_packed ? (n_tiles16 >= 3072 ? 10 : 7) : (n_tiles16 >= 3072 ? 7 : 6);
+    if (p.M <= 16 && g_mfma_tile == 0) use_tile = p.M >= tile_min_m && n_tiles16 >= 1536 && !partial;
     if (EPI == EPI_RESID && p.xb_out) use_tile = false;   // the hand-over to the next product lives in the per-tile kernel
     if (use_tile && tile_shape_ok(p.out_rows, p.in_dim)) {
         if (p.M <= 16) {
