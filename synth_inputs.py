@@ -34,6 +34,11 @@ TINY_GQA_BF16 = dict(name="tiny_gqa_bf16", n_layers=3, n_draft_layers=1, d_model
                      n_heads=4, n_kv_heads=2, head_dim=128, d_ff=1024, vocab=1024,
                      rms_eps=1e-6, rope_base=10000.0, dtype="bf16")
 
+# a bf16 model with 64-wide heads (8 query heads on 2 KV heads)
+TINY_HD64_BF16 = dict(name="tiny_hd64_bf16", n_layers=3, n_draft_layers=2, d_model=512,
+                      n_heads=8, n_kv_heads=2, head_dim=64, d_ff=768, vocab=512,
+                      rms_eps=1e-5, rope_base=10000.0, dtype="bf16")
+
 LLAMA13B = dict(name="llama2-13b-shape", n_layers=40, n_draft_layers=5, d_model=5120,
                 n_heads=40, n_kv_heads=40, head_dim=128, d_ff=13824, vocab=32000,
                 rms_eps=1e-5, rope_base=10000.0, dtype="bf16")

@@ -221,6 +221,53 @@ def test_generate_matches_oracle_stream(name, temp, mode):
         assert st.accepted > 5
 
 
+@pytest.mark.parametrize("tiled", [0, 1])
+@pytest.mark.parametrize("tree", [0, 3])
+def test_heads_of_64_channels_bf16_match_oracle(tiled, tree):
+    """A bf16 model with head_dim 64 (four 16-row QKV tiles per head, the 64-channel MFMA attention),
+    8 query heads on 2 KV heads, N = 2: prefill across a page boundary, draft and verify logits, caches;
+    chain and candidate tree; both weight layouts."""
+    require_gpu()
+    shape = si.TINY_HD64_BF16
+    tol = tol_of(shape)
+    o, g = make_pair(shape, 17, 128, 0.0 if tree else 1.0, k_cap=4, gamma=0.05, weight_layout=tiled, tree_width=tree, kv_page=16)
+    prompt = si.make_prompt(45, shape["vocab"], 4)
+    t_ref = o.prefill(prompt)
+    g.prefill(prompt)
+    assert rel_err(g.verify_logits(0), o.prefill_logits) < tol
+    g.force_pending(t_ref)
+    for K in (4, 2):
+        if tree:
+            kids = [o.draft_step_tree() for _ in range(K)]
+            g.force_drafts([t for k in kids for t in k])
+        else:
+            g.force_drafts([o.draft_step() for _ in range(K)])
+        for _ in range(K):
+            g.draft_step(sync=False)
+        for i in range(K):
+            assert rel_err(g.draft_logits(i), o.q_logits[i]) < tol, ("draft", K, i)
+        g.verify()
+        if tree:
+            a, y, branch = o.verify_accept_tree()
+            assert rel_err(g.verify_logits(0), o.tree_logits[()]) < tol
+            for i in range(1, K + 1):
+                for j in range(tree):
+                    assert rel_err(g.verify_logits(1 + (i - 1) * tree + j), o.tree_logits[(i, j)]) < tol, ("node", K, i, j)
+            g.accept()
+            o.rollback_tree(0, y, [])
+            g.rollback(0)
+        else:
+            pl = o.verify()
+            for i in range(K + 1):
+                assert rel_err(g.verify_logits(i), pl[i]) < tol, ("verify", K, i)
+            a, y = o.accept()
+            g.accept()
+            o.rollback(a, y)
+            g.rollback(a)
+        g.force_pending(y)
+    _check_caches(o, g, o.kv_len, tol)
+
+
 @pytest.mark.parametrize("temp,tree", [(1.0, 0), (0.0, 0), (0.0, 2)])
 def test_tiled_weight_layout_generates_the_same_tokens(temp, tree):
     """Whole generations (prefill blocks, draft steps, verify blocks of every size, all epilogues) from
