@@ -287,7 +287,8 @@ int eesd_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /* Launch-shape knobs for benchmark sweeps (process-wide; 0 restores the built-in heuristic):
  * "valu_nw", "valu_tpw", "valu_rp", "mfma_nw", "mfma_ksplit", "fuse_norm", "mfma_tile", "tile_kc", "tile_nwt", "pf_kc",
- * "attn_split", "mfma_min_m". */
+ * "attn_split", "mfma_min_m", "nw_plain", "nw_resid", "nw_swiglu", "nw_qkv" (waves per workgroup of the per-tile
+ * product by epilogue). */
 int eesd_set_tunable(const char* name, int value);
 
 /* ---- stand-alone kernels (device buffers in, host results out) ----------------------- */
