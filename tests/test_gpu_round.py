@@ -454,14 +454,14 @@ def test_schedule_and_fixed_controller_modes():
         g.set_draft_schedule([9])
 
 
-@pytest.mark.parametrize("name", list(SHAPES))
-def test_same_seed_twice_is_bit_identical(name):
-    """No atomics in any reduction: two runs give the same bits (tokens and logits)."""
+@pytest.mark.parametrize("name,tiled", [("tiny_fp32", 0), ("gqa_bf16", 0), ("gqa_bf16", 1)])
+def test_same_seed_twice_is_bit_identical(name, tiled):
+    """No atomics in any reduction: two runs give the same bits (tokens and logits), in either weight layout."""
     require_gpu()
     shape = SHAPES[name]
     runs = []
     for _ in range(2):
-        _, g = make_pair(shape, 13, 160, 1.0, k_cap=5, seed=21)
+        _, g = make_pair(shape, 13, 160, 1.0, k_cap=5, seed=21, weight_layout=tiled)
         out, st = g.generate(si.make_prompt(45, shape["vocab"], 2), 40)
         g.verify()                      # one more plain target step to look at logits
         runs.append((out, st.drafted, st.accepted, g.verify_logits(0).copy()))
