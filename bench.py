@@ -222,6 +222,7 @@ def main():
     ms_draft = sum(s.ms_draft for s in stats) / max(1, sum(s.drafted for s in stats))
     ms_verify = sum(s.ms_verify for s in stats) / max(1, rounds)
     ms_accept = sum(s.ms_accept for s in stats) / max(1, rounds)
+    ms_other = sum(s.ms_other for s in stats) / max(1, rounds)       # host turn-around between rounds
     N, L = shape["n_draft_layers"], shape["n_layers"]
     ctx_mid = n_prompt + max_new // 2
     b_draft = pass_bytes(shape, N + 1, True, ctx_mid, si)
@@ -253,7 +254,7 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": stored_traffic(args.workload), "launches_timed": n_launch, "avg_kernel_us": avg_kernel_s * 1e6,
                      "bytes_per_launch": kernel_bytes},
-        "passes": {"draft_step_ms": ms_draft, "verify_ms": ms_verify, "accept_ms": ms_accept,
+        "passes": {"draft_step_ms": ms_draft, "verify_ms": ms_verify, "accept_ms": ms_accept, "host_gap_ms_per_round": ms_other,
                    "draft_step_GBps": b_draft / (ms_draft * 1e-3) / 1e9 if ms_draft else None,
                    "verify_GBps": b_verify / (ms_verify * 1e-3) / 1e9 if ms_verify else None,
                    "draft_step_bytes": b_draft, "verify_bytes": b_verify,
