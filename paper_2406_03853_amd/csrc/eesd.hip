@@ -38,7 +38,7 @@ static int g_mfma_nw = 0;      // waves per workgroup of the MFMA product
 static int g_attn_split = 0;   // keys per attention split
 static int g_tile_kc = 0;      // 512: the tile kernel takes 512-column chunks for verify-sized blocks (default 256)
 static int g_tile_nwt = 0;     // 4 / 8: tiles per workgroup of the tile kernel for verify-sized blocks (0 = by tile count)
-static int g_fuse_norm = -1;   // residual -> next product hand-over without resid_norm_kernel: 1 on, 0 off, -1 by model width
+static int g_fuse_norm = -1;   // residual -> next product hand-over without resid_norm_kernel: 1 both products, 2 attention output only, 3 FFN down only, 0 off, -1 by model width
 static int g_nw_epi[4] = {0, 0, 0, 0};   // waves per workgroup of the per-tile product by epilogue (plain, resid, swiglu, qkv)
 static int g_pf_kc = 0;        // 256: prefill blocks take 256-column chunks (default 128)
 static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: by rows and tile count
@@ -476,16 +476,19 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
         // Decoding blocks (<= 16 rows): the residual products keep K inside the workgroup and hand
         // gain * x and partial sums of squares to their consumer (no kernel in between).  Prefill
         // blocks split K over workgroups and fold the partial sums in resid_norm_kernel.
-        // (measured: -10 us per 70B-shape layer; at d_model = 5120 the 320-tile residual products lose
-        // more without their K split than the two small kernels cost, so narrow models keep those)
-        const bool fused = M <= MAX_ROWS && (g_fuse_norm < 0 ? d / 16 >= 448 : g_fuse_norm != 0);
+        // (measured: -10 us per 70B-shape layer; at d_model = 5120 the 320-tile FFN-down product loses more
+        // without its K split than the small kernel costs, so narrow models hand over after the
+        // attention output only: -2 us per 13B-shape layer)
+        const bool fuse_ok = M <= MAX_ROWS;
+        const bool fused_wo = fuse_ok && (g_fuse_norm < 0 ? true : (g_fuse_norm == 1 || g_fuse_norm == 2));
+        const bool fused_down = fuse_ok && (g_fuse_norm < 0 ? d / 16 >= 448 : (g_fuse_norm == 1 || g_fuse_norm == 3));
         GemmP p = gemm_base(lw.wqkv, c->xb, d, M, qkv_rows, d);
         fill_qkv(c, p, cache, pos0, 0);
         take_xb(c, p);
         if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
         if ((rc = launch_attention(c, cache, M, pos0, true))) return rc;
         p = gemm_base(lw.wo, c->ab, qd, M, d, qd);
-        if (fused) {
+        if (fused_wo) {
             p.Y = c->x; p.ldy = d;
             fuse_next(c, p, lw.ffn_norm);
             if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
@@ -502,7 +505,7 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
         take_xb(c, p);
         if ((rc = gemm_launch<EPI_SWIGLU>(c, true, p))) return rc;
         p = gemm_base(lw.w_down, c->actb, f, M, d, f);
-        if (fused) {
+        if (fused_down) {
             p.Y = c->x; p.ldy = d;
             fuse_next(c, p, next_gain);
             if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;

@@ -80,7 +80,7 @@ def test_teacher_forced_rounds_match_oracle(name, temp, reuse):
     assert (s.alpha, s.beta) == (o.ts.alpha, o.ts.beta)
 
 
-@pytest.mark.parametrize("path,ksplit", [("valu", 0), ("mfma", 1), ("mfma", 2), ("mfma", 8), ("auto", 4), ("tile", 0), ("tile", 2), ("nofuse", 0), ("nofuse", 4), ("tile_nofuse", 2), ("fuse", 0), ("tile_fuse", 0)])
+@pytest.mark.parametrize("path,ksplit", [("valu", 0), ("mfma", 1), ("mfma", 2), ("mfma", 8), ("auto", 4), ("tile", 0), ("tile", 2), ("nofuse", 0), ("nofuse", 4), ("tile_nofuse", 2), ("fuse", 0), ("tile_fuse", 0), ("fuse_wo", 0), ("fuse_down", 4)])
 def test_kernel_families_and_k_splits_match_oracle(path, ksplit):
     """The bf16 model with one kernel family forced for every pass (single-row MFMA, multi-row
     VALU) and with the residual products split over 1..8 workgroups along K."""
@@ -88,11 +88,11 @@ def test_kernel_families_and_k_splits_match_oracle(path, ksplit):
     import paper_2406_03853_amd as pk
     shape = SHAPES["gqa_bf16"]
     tol = tol_of(shape)
-    gp = {"valu": pk.GEMM_VALU, "mfma": pk.GEMM_MFMA, "auto": pk.GEMM_AUTO, "tile": pk.GEMM_AUTO, "nofuse": pk.GEMM_AUTO, "tile_nofuse": pk.GEMM_AUTO, "fuse": pk.GEMM_AUTO, "tile_fuse": pk.GEMM_AUTO}[path]
+    gp = {"valu": pk.GEMM_VALU, "mfma": pk.GEMM_MFMA, "auto": pk.GEMM_AUTO, "tile": pk.GEMM_AUTO, "nofuse": pk.GEMM_AUTO, "tile_nofuse": pk.GEMM_AUTO, "fuse": pk.GEMM_AUTO, "tile_fuse": pk.GEMM_AUTO, "fuse_wo": pk.GEMM_AUTO, "fuse_down": pk.GEMM_AUTO}[path]
     try:
         pk.set_tunable("mfma_ksplit", ksplit)
         pk.set_tunable("mfma_tile", 1 if path.startswith("tile") else 0)
-        pk.set_tunable("fuse_norm", 0 if path.endswith("nofuse") else (1 if path.endswith("fuse") else -1))
+        pk.set_tunable("fuse_norm", 0 if path.endswith("nofuse") else 1 if path.endswith("fuse") else 2 if path == "fuse_wo" else 3 if path == "fuse_down" else -1)
         o, g = make_pair(shape, 11, 96, 1.0, k_cap=4, gemm_path=gp)
         prompt = si.make_prompt(21, shape["vocab"], 5)
         t_ref = o.prefill(prompt)
