@@ -407,3 +407,49 @@ def test_stats_counters(tiny_np):
     s = o.stats
     assert len(out) == 30 and s.generated == 30 and s.drafted <= 3 * s.rounds
     assert 0 <= s.accepted <= s.drafted and abs(s.v_d - s.accepted / s.drafted) < 1e-15
+
+
+def test_stats_hand_computed_rounds(tiny_np):
+    """Appendix D on a hand-made run: three rounds with K = 3, 2, 4 drafts and a = 1, 2, 0 accepted, the
+    first token from prefill: N_all_draft = 9, N_right = 3, L = 1 + (2 + 3 + 1) = 7, so v_d = 3/9,
+    r_d = 3/7 and HM = 2 (1/3)(3/7) / (1/3 + 3/7) = 3/8."""
+    o = orc.OracleEESD(tiny_np, 64, 1.0)
+    n_out = 1
+    for K, a in ((3, 1), (2, 2), (4, 0)):
+        o.drafts = [0] * K
+        o.rollback(a, 0)
+        n_out += a + 1
+    o.stats.generated = n_out
+    s = o.stats
+    assert (s.rounds, s.drafted, s.accepted, s.generated) == (3, 9, 3, 7)
+    assert abs(s.v_d - 3 / 9) < 1e-15 and abs(s.r_d - 3 / 7) < 1e-15
+    assert abs(orc.harmonic_mean_pct(s.v_d, s.r_d) - 37.5) < 1e-12
+    # r_d is not v_d: a dropped "generated" (or the draft count in its place) fails here
+    assert abs(s.r_d - s.v_d) > 0.09
+
+
+def test_shapes_reproduce_printed_trainable_parameter_counts():
+    """Section 3.1: the early-exit layer and its head are initialised from the target's last layer and LM
+    head, so they have a decoder layer's and a full head's shape; their sizes must give the trainable
+    parameters the main results table prints, and ten d x d matrices plus the 2 x 2d projection of
+    Eq. 5 the predictor's."""
+    shapes = {s["name"]: s for s in (si.LLAMA70B, si.LLAMA13B)}
+    unit = {"B": 1e9, "M": 1e6}
+    rows = _rows("paper_param_counts.txt")
+    assert len(rows) == 2
+    for name, trainable, tu, predictor, pu in rows:
+        sh = shapes[name]
+        d = sh["d_model"]
+        n_train = si.layer_param_count(sh) + sh["vocab"] * d + d          # layer (with its two norms) + final norm + head
+        n_pred = 10 * d * d + 2 * 2 * d
+        digits = len(trainable.split(".")[1]) if "." in trainable else 0
+        assert round(n_train / unit[tu], digits) == float(trainable), (name, n_train)
+        digits = len(predictor.split(".")[1]) if "." in predictor else 0
+        assert round(n_pred / unit[pu], digits) == float(predictor), (name, n_pred)
+        cw = si.make_cali_weights(si.reduced_depth(dict(sh, d_model=64), 2, 1), 0)
+        assert tuple(cw["w"].shape) == (10, 64, 64) and tuple(cw["wp"].shape) == (2, 128)
+    # the weight container really has those shapes (checked on a narrow model of the same family)
+    small = dict(si.LLAMA70B, d_model=256, n_heads=8, n_kv_heads=2, head_dim=32, d_ff=512, vocab=640, n_layers=2, n_draft_layers=1, dtype="f32")
+    w = si.make_weights(small, seed=0)
+    n = sum(int(w["ee_layer"][k].numel()) for k in si.LAYER_KEYS) + int(w["ee_head"].numel()) + int(w["ee_norm"].numel())
+    assert n == si.layer_param_count(small) + small["vocab"] * small["d_model"] + small["d_model"]
