@@ -309,14 +309,18 @@ int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out
                  int32_t dtype, int32_t path, int32_t weight_layout, void* hip_stream);
 
 /* Rearranges one bf16 weight matrix (DEVICE, row-major [out_rows][in_dim]) into the tile-major layout
- * the MFMA kernel family reads with one contiguous 1 KB access per operand (EESD_WEIGHTS_TILED):
- * tiles of 16 rows, each stored as in_dim/32 blocks of 1 KB, a block holding 32 columns of the 16
- * rows in the lane order of the MFMA operand.  Which 16 rows form a tile follows the epilogue the
- * matrix feeds: kind EESD_PACK_PLAIN (LM heads, attention output, FFN down, the calibration
- * matrices): 16 consecutive rows; EESD_PACK_GATE_UP (fused gate|up, out_rows = 2 d_ff): 8 gate rows
- * and their 8 up rows; EESD_PACK_QKV (fused q|k|v; head_dim given): 8 rows of a head and their
- * rotary partners head_dim/2 further.  dst: DEVICE, out_rows * in_dim elements, must not overlap
- * src.  out_rows % 16 == 0 (QKV: % head_dim), in_dim % 128 == 0.  Does not synchronise. */
+ * the MFMA kernel family streams with contiguous reads (EESD_WEIGHTS_TILED).  The rows are dealt to row
+ * groups in units of 4 rows; a group is stored contiguously as blocks of 32 columns, each block holding
+ * the group's tiles of 16 rows (the last one possibly shorter) in the lane order of the MFMA operand.
+ * Matrices with at most one 16-row tile per compute unit of the CURRENT DEVICE, or with at least four,
+ * keep one tile per group; those in between are dealt to exactly one group per compute unit, so that
+ * every CU streams the same number of bytes (the layout therefore depends on the device's CU count:
+ * pack on the device that will run the model).  Which rows form a tile follows the epilogue the matrix
+ * feeds: kind EESD_PACK_PLAIN (LM heads, attention output, FFN down, the calibration matrices):
+ * consecutive rows; EESD_PACK_GATE_UP (fused gate|up, out_rows = 2 d_ff): 8 gate rows and their 8 up
+ * rows; EESD_PACK_QKV (fused q|k|v; head_dim given): 8 rows of a head and their rotary partners
+ * head_dim/2 further.  dst: DEVICE, out_rows * in_dim elements, must not overlap src.
+ * out_rows % 16 == 0 (QKV: % head_dim), in_dim % 128 == 0.  Does not synchronise. */
 int eesd_pack_weight(const void* src, void* dst, int32_t out_rows, int32_t in_dim, int32_t kind, int32_t head_dim,
                      void* hip_stream);
 

@@ -132,6 +132,8 @@ struct eesd_ctx {
     bf16_t* h_tb;                         // bf16 copy of h_t (operand of the MFMA product)
     float* hn_rows;                       // verify_reuse: layer-N hidden state of every draft step's input row [k_cap][d]
     int max_splits;
+    int n_cu;              // compute units of the device (fixes the row groups of the tile-major weight layout)
+    int ssq_slots;         // partial sums of squares a residual product leaves per row
     int row_cap;           // rows the activation buffers hold (16, or PREFILL_ROWS)
     hipEvent_t ev[4];
 
@@ -173,6 +175,19 @@ static KVView kv_view(const eesd_ctx* c, int cache) {
     v.head_dim = c->cfg.head_dim;
     v.v_transposed = is_bf16(c) ? 1 : 0;
     return v;
+}
+
+// compute units of the current device (cached per device)
+static int device_cu_count() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (!cached[dev]) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cached[dev] = n;
+    }
+    return cached[dev];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -252,7 +267,29 @@ static hipError_t launch_tile_t(const GemmP& p, int ksplit, hipStream_t st) {
     auto fn = gemm_tile_kernel<EPI, NB, KC, NWT>;
     hipError_t e = allow_lds((const void*)fn, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, dim3(p.out_rows / (16 * NWT), ksplit), dim3(64 * NWT), lds, st, p);
+    const bool grouped = p.w_packed && p.n_groups != p.out_rows / 16;
+    if (grouped && NWT < GRP_MAX_TILES) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fn, dim3(grouped ? p.n_groups : p.out_rows / (16 * NWT), ksplit), dim3(64 * NWT), lds, st, p);
+    return hipGetLastError();
+}
+
+// one workgroup per row group (tile-major matrices dealt to one group per CU), blocks of <= 16 rows
+template <int EPI>
+static hipError_t launch_group(const GemmP& p, hipStream_t st) {
+    if (EPI == EPI_RESID && p.y_partial) return hipErrorInvalidValue;
+    const int units = p.out_rows / 4, max_units = (units + p.n_groups - 1) / p.n_groups;
+    const int tmax = (max_units * 4 + 15) / 16;
+    int nw = 8;
+    const int steps = p.in_dim / 128;
+    while (nw > 1 && steps / nw < 2) nw >>= 1;
+    const size_t lds = (size_t)nw * tmax * 1024;
+    switch (tmax) {
+        case 1: hipLaunchKernelGGL((gemm_group_kernel<EPI, 1>), dim3(p.n_groups), dim3(nw * 64), lds, st, p); break;
+        case 2: hipLaunchKernelGGL((gemm_group_kernel<EPI, 2>), dim3(p.n_groups), dim3(nw * 64), lds, st, p); break;
+        case 3: hipLaunchKernelGGL((gemm_group_kernel<EPI, 3>), dim3(p.n_groups), dim3(nw * 64), lds, st, p); break;
+        case 4: hipLaunchKernelGGL((gemm_group_kernel<EPI, 4>), dim3(p.n_groups), dim3(nw * 64), lds, st, p); break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
@@ -265,6 +302,15 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
     // per workgroup when there are very many.  Prefill blocks (M > 16) always take the tile kernel.
     const int n_tiles16 = p.out_rows / 16;
     const bool partial = EPI == EPI_RESID && p.y_partial;
+    if (p.w_packed && p.n_groups != n_tiles16) {
+        // one row group per CU: decoding blocks take the group kernel, prefill blocks the tile kernel with a wave per tile of the group
+        if (p.M <= 16) return launch_group<EPI>(p, st);
+        if (p.in_dim % GT_KC_MIN) return hipErrorInvalidValue;
+        if (p.M <= 32) return launch_tile_t<EPI, 2, 256, 4>(p, ksplit, st);
+        if (p.M <= 64) return launch_tile_t<EPI, 4, 256, 4>(p, ksplit, st);
+        if (p.M <= 128) return g_pf_kc == 256 ? launch_tile_t<EPI, 8, 256, 4>(p, ksplit, st) : launch_tile_t<EPI, 8, 128, 4>(p, ksplit, st);
+        return hipErrorInvalidValue;
+    }
     bool use_tile = p.M > 16;
     if (p.M <= 16 && g_mfma_tile == 1) use_tile = true;
     // crossover rows (measured): row-major weights 6, 7 for the widest products; tile-major weights, whose
@@ -343,6 +389,7 @@ static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
     if (mfma) {
         GemmP pm = p;
         pm.w_packed = c->cfg.weight_layout == EESD_WEIGHTS_TILED;
+        pm.n_groups = pm.w_packed ? pack_n_groups(pm.out_rows, c->n_cu) : 0;
         HIP_TRY(c, launch_mfma<EPI>(pm, ksplit, c->stream));
     } else {
         HIP_TRY(c, launch_valu<EPI>(p, is_bf16(c), c->stream));
@@ -358,7 +405,7 @@ static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
 static void take_xb(const eesd_ctx* c, GemmP& p) {
     if (c->xb_has_ssq) {
         p.ssq_in = c->ssq;
-        p.ssq_tiles = c->cfg.d_model / 16;
+        p.ssq_tiles = c->ssq_slots;
         p.ssq_eps = c->cfg.rms_eps;
     }
 }
@@ -369,6 +416,7 @@ static void fuse_next(eesd_ctx* c, GemmP& p, const void* gain) {
     p.ld_xb = c->cfg.d_model;
     p.gain_next = gain;
     p.ssq_out = c->ssq;
+    p.ssq_tiles = c->ssq_slots;
 }
 
 static GemmP gemm_base(const void* W, const void* X, int ldx, int M, int out, int in) {
@@ -479,9 +527,11 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
         // (measured: -10 us per 70B-shape layer; at d_model = 5120 the 320-tile FFN-down product loses more
         // without its K split than the small kernel costs, so narrow models hand over after the
         // attention output only: -2 us per 13B-shape layer)
+        // (matrices dealt to one row group per CU always keep K whole and hand over: the group kernel has no other form)
         const bool fuse_ok = M <= MAX_ROWS;
-        const bool fused_wo = fuse_ok && (g_fuse_norm < 0 ? true : (g_fuse_norm == 1 || g_fuse_norm == 2));
-        const bool fused_down = fuse_ok && (g_fuse_norm < 0 ? d / 16 >= 448 : (g_fuse_norm == 1 || g_fuse_norm == 3));
+        const bool grouped = c->cfg.weight_layout == EESD_WEIGHTS_TILED && pack_n_groups(d, c->n_cu) != d / 16;
+        const bool fused_wo = fuse_ok && (grouped || g_fuse_norm < 0 ? true : (g_fuse_norm == 1 || g_fuse_norm == 2));
+        const bool fused_down = fuse_ok && (grouped || (g_fuse_norm < 0 ? d / 16 >= 448 : (g_fuse_norm == 1 || g_fuse_norm == 3)));
         GemmP p = gemm_base(lw.wqkv, c->xb, d, M, qkv_rows, d);
         fill_qkv(c, p, cache, pos0, 0);
         take_xb(c, p);
@@ -548,7 +598,14 @@ static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
     const char* wkv = (const char*)c->w.ee_layer.wqkv + (size_t)g.n_heads * hd * d * esz;
     const int rows = 2 * g.n_kv_heads * hd;
     int rc;
-    if (mfma) {
+    if (mfma && c->cfg.weight_layout == EESD_WEIGHTS_TILED) {
+        // tile-major: the whole fused matrix is given; tiles and groups of query heads are skipped
+        GemmP p = gemm_base(c->w.ee_layer.wqkv, c->xb, d, M, (g.n_heads + 2 * g.n_kv_heads) * hd, d);
+        fill_qkv(c, p, g.n_layers, pos0, 0);
+        p.head_min = g.n_heads;
+        take_xb(c, p);
+        if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
+    } else if (mfma) {
         GemmP p = gemm_base(wkv, c->xb, d, M, rows, d);
         fill_qkv(c, p, g.n_layers, pos0, g.n_heads);
         take_xb(c, p);
@@ -922,6 +979,12 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
 
     const int d = g.d_model, f = g.d_ff, V = g.vocab;
     c->max_splits = 64;
+    c->n_cu = device_cu_count();
+    if (c->n_cu < 1) return bail(EESD_EDEVICE);
+    {
+        const bool grouped = g.weight_layout == EESD_WEIGHTS_TILED && pack_n_groups(d, c->n_cu) != d / 16;
+        c->ssq_slots = grouped ? c->n_cu * GRP_MAX_TILES : d / 16;
+    }
     {
         const int qkv_rows = (g.n_heads + 2 * g.n_kv_heads) * g.head_dim, kv_rows = 2 * g.n_kv_heads * g.head_dim;
         bool tiled = g.dtype == EESD_DTYPE_BF16 && g.gemm_path != EESD_GEMM_VALU && tile_shape_ok(qkv_rows, d) && tile_shape_ok(kv_rows, d) &&
@@ -940,8 +1003,8 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if ((rc = dev_alloc(c, &c->part_o, (size_t)MAX_ROWS * g.n_heads * c->max_splits * g.head_dim))) return bail(rc);
     if ((rc = dev_alloc(c, &c->part_ml, (size_t)MAX_ROWS * g.n_heads * c->max_splits * 2))) return bail(rc);
     if ((rc = dev_alloc(c, &c->part, (size_t)MFMA_MAX_KSPLIT * R * d))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->ssq, (size_t)(d / 16) * MAX_ROWS))) return bail(rc);
-    hipMemset(c->ssq, 0, sizeof(float) * (d / 16) * MAX_ROWS);
+    if ((rc = dev_alloc(c, &c->ssq, (size_t)c->ssq_slots * MAX_ROWS))) return bail(rc);
+    hipMemset(c->ssq, 0, sizeof(float) * c->ssq_slots * MAX_ROWS);
     if ((rc = dev_alloc(c, &c->xb, R * d))) return bail(rc);
     if ((rc = dev_alloc(c, &c->ab, R * qd))) return bail(rc);
     if ((rc = dev_alloc(c, &c->actb, R * f))) return bail(rc);
@@ -1609,9 +1672,12 @@ extern "C" int eesd_pack_weight(const void* src, void* dst, int32_t out_rows, in
     else if (kind == EESD_PACK_QKV) epi = EPI_QKV;
     else return EESD_EINVAL;
     if (!mfma_shape_ok(out_rows, in_dim, epi, head_dim)) return EESD_EINVAL;
-    const long long pieces = (long long)out_rows * in_dim / 8;
-    hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream, (const bf16_t*)src,
-                       (bf16_t*)dst, out_rows, in_dim, epi, head_dim);
+    if (out_rows % 16) return EESD_EINVAL;
+    const int n_cu = device_cu_count();
+    if (n_cu < 1) return EESD_EDEVICE;
+    const int n_groups = pack_n_groups(out_rows, n_cu);
+    hipLaunchKernelGGL(pack_weight_kernel, dim3(n_groups), dim3(256), 0, (hipStream_t)hip_stream, (const bf16_t*)src,
+                       (bf16_t*)dst, out_rows, in_dim, epi, head_dim, n_groups);
     return hipGetLastError() == hipSuccess ? EESD_OK : EESD_EDEVICE;
 }
 
@@ -1627,7 +1693,9 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
     if (path == EESD_GEMM_MFMA && !b16) return EESD_EINVAL;
     if (mfma) {
         if (!mfma_shape_ok(out, in, EPI_PLAIN, 0)) return EESD_EINVAL;
-        if (M > MAX_ROWS && !tile_shape_ok(out, in)) return EESD_EINVAL;
+        const int n_groups = weight_layout == EESD_WEIGHTS_TILED ? pack_n_groups(out, device_cu_count()) : 0;
+        const bool grouped = n_groups && n_groups != out / 16;
+        if (M > MAX_ROWS && (grouped ? in % GT_KC_MIN != 0 : !tile_shape_ok(out, in))) return EESD_EINVAL;
         // bf16 staging rows of the activations: one buffer per process, grown on demand, kept
         static bf16_t* xb = nullptr;
         static size_t xb_elems = 0;
@@ -1646,6 +1714,7 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
             GemmP p = gemm_base(W, xb, in, M, out, in);
             p.Y = Y; p.ldy = out;
             p.w_packed = weight_layout == EESD_WEIGHTS_TILED;
+            p.n_groups = n_groups;
             e = launch_mfma<EPI_PLAIN>(p, 1, st);
         }
         return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
