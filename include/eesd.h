@@ -320,6 +320,17 @@ int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out
  * consecutive rows; EESD_PACK_GATE_UP (fused gate|up, out_rows = 2 d_ff): 8 gate rows and their 8 up
  * rows; EESD_PACK_QKV (fused q|k|v; head_dim given): 8 rows of a head and their rotary partners
  * head_dim/2 further.  dst: DEVICE, out_rows * in_dim elements, must not overlap src.
+/* eesd_op_gemm for callers that cannot allocate (code under HIP graph capture, serving loops and harnesses that
+ * forbid hipMalloc): the same product on bf16 weights (MFMA kernel family; W, X, Y, weight_layout as above), but
+ * the bf16 staging rows of the activations live in a fixed 1 MiB device array of this library (per GPU, held until
+ * the process ends) instead of a buffer that eesd_op_gemm grows with hipMalloc.  No allocation of any kind is made.
+ * Limits: 1 <= M <= 16, 128 <= in <= 32768, else EESD_ERANGE; out % 16 == 0, in % 128 == 0 else EESD_EINVAL.
+ * All calls on one GPU share that array, which keeps the last call's contents (nothing in it has to start at zero:
+ * rows >= M are never used): calls that overlap on one GPU - different streams, different threads - race.
+ * Does not synchronise. */
+int eesd_op_gemm_noalloc(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,
+                         int32_t weight_layout, void* hip_stream);
+
  * out_rows % 16 == 0 (QKV: % head_dim), in_dim % 128 == 0.  Does not synchronise. */
 int eesd_pack_weight(const void* src, void* dst, int32_t out_rows, int32_t in_dim, int32_t kind, int32_t head_dim,
                      void* hip_stream);

@@ -83,7 +83,7 @@ EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "ee
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
            "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_set_calibration", "eesd_cali_score",
-           "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm", "eesd_pack_weight"]
+           "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm", "eesd_op_gemm_noalloc", "eesd_pack_weight"]
 
 
 def lib() -> C.CDLL:
@@ -132,6 +132,7 @@ def lib() -> C.CDLL:
     L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
     L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, I32, VP]
     L.eesd_pack_weight.argtypes = [VP, VP, I32, I32, I32, I32, VP]
+    L.eesd_op_gemm_noalloc.argtypes = [VP, VP, VP, I32, I32, I32, I32, VP]
     for name in EXPORTS:
         if name not in ("eesd_destroy", "eesd_last_error", "eesd_host_uniform"):
             getattr(L, name).restype = C.c_int
@@ -401,6 +402,13 @@ def pack_weight(W, kind: int = PACK_PLAIN, head_dim: int = 0, stream: int = 0):
     if rc:
         raise EesdError(rc, "eesd_pack_weight")
     return dst
+
+
+def op_gemm_noalloc(W, X, Y, stream: int = 0, weight_layout: int = WEIGHTS_ROW_MAJOR) -> None:
+    M, inn = X.shape
+    rc = lib().eesd_op_gemm_noalloc(W.data_ptr(), X.data_ptr(), Y.data_ptr(), M, W.shape[0], inn, weight_layout, C.c_void_p(stream))
+    if rc:
+        raise EesdError(rc, "eesd_op_gemm_noalloc")
 
 
 def pack_weights(weights: dict) -> dict:

@@ -1725,3 +1725,39 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
     hipError_t e = launch_valu<EPI_PLAIN>(p, b16, st);
     return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
 }
+
+// ---------------------------------------------------------------------------------------------
+// eesd_op_gemm without any allocation: the bf16 staging rows of the activations live in a fixed
+// device array of this library instead of a buffer grown with hipMalloc.
+// ---------------------------------------------------------------------------------------------
+#define NOALLOC_MAX_ROWS MAX_ROWS
+#define NOALLOC_MAX_IN 32768
+static __device__ __align__(256) unsigned char scratch[(size_t)NOALLOC_MAX_ROWS * NOALLOC_MAX_IN * sizeof(bf16_t)];   // 1 MiB per GPU, held until the process ends
+static void* g_scratch_ptr[64] = {nullptr};   // the array's address on each device
+
+extern "C" int eesd_op_gemm_noalloc(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in, int32_t weight_layout,
+                                    void* hip_stream) {
+    if (!W || !X || !Y) return EESD_EINVAL;
+    if (M < 1 || M > NOALLOC_MAX_ROWS || in < 128 || in > NOALLOC_MAX_IN) return EESD_ERANGE;   // beyond what the fixed staging array holds
+    if (weight_layout != EESD_WEIGHTS_ROW_MAJOR && weight_layout != EESD_WEIGHTS_TILED) return EESD_EINVAL;
+    if (!mfma_shape_ok(out, in, EPI_PLAIN, 0)) return EESD_EINVAL;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return EESD_EDEVICE;
+    if (!g_scratch_ptr[dev]) {     // once per device, with that device current: every GPU holds its own copy of the array
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return EESD_EDEVICE;
+        g_scratch_ptr[dev] = ptr;
+    }
+    bf16_t* xb = (bf16_t*)g_scratch_ptr[dev];
+    const int n_cu = device_cu_count();
+    if (n_cu < 1) return EESD_EDEVICE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // rows >= M of the staging array keep whatever the last call left: no kernel below stores a value computed from them
+    hipLaunchKernelGGL(to_bf16_kernel, dim3((in + 255) / 256, M), dim3(256), 0, st, X, in, in, xb, in);
+    if (hipGetLastError() != hipSuccess) return EESD_EDEVICE;
+    GemmP p = gemm_base(W, xb, in, M, out, in);
+    p.Y = Y; p.ldy = out;
+    p.w_packed = weight_layout == EESD_WEIGHTS_TILED;
+    p.n_groups = p.w_packed ? pack_n_groups(out, n_cu) : 0;
+    return launch_mfma<EPI_PLAIN>(p, 1, st) == hipSuccess ? EESD_OK : EESD_EDEVICE;
+}
