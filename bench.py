@@ -104,7 +104,7 @@ def latency_sweep(ctx, torch, cache_tokens, k_cap, b_draft, shape, si):
             ctx.verify()
             ev[2].record()
             ctx.accept()
-            ctx.rollback(0)
+            ctx.rollback_forced(0, 1)
             if r:
                 td += ev[0].elapsed_time(ev[1])
                 tv += ev[1].elapsed_time(ev[2])

@@ -179,10 +179,13 @@ int eesd_accept(eesd_ctx* ctx, const double* uniforms_or_null, int32_t* n_accept
  * Valid between eesd_accept and the next eesd_accept. */
 int eesd_accepted_tokens(eesd_ctx* ctx, int32_t* toks, int32_t cap, int32_t* n);
 
-/* Keeps the accepted prefix: the valid length of every layer's KV cache (and of the
- * early-exit layer's) becomes base + n_accepted + 1, whole pages past it return to the
- * pool, the token eesd_accept returned becomes the pending token, and the controller's
- * posterior is updated (Eq. 3-4).  0 <= n_accepted <= K else EESD_ERANGE. */
+/* Keeps the accepted prefix (Algorithm 1, steps 16-18; the rejected and the unjudged drafts are
+ * discarded, Appendix F): the valid length of every layer's KV cache (and of the early-exit layer's)
+ * becomes base + n_accepted + 1, whole pages past it return to the pool, the token eesd_accept
+ * returned becomes the pending token, and the controller's posterior is updated (Eq. 3-4).
+ * n_accepted must be the a that eesd_accept returned - any other count would commit drafts the
+ * accept rule rejected, or drop ones it kept, and the output would no longer be distributed as
+ * auto-regressive decoding - else EESD_ERANGE. */
 int eesd_rollback(eesd_ctx* ctx, int32_t n_accepted);
 
 /* Algorithm 1 end to end: prefill, then rounds until max_new tokens exist.  prompt: HOST,
@@ -259,7 +262,12 @@ enum {
     EESD_READ_KV_LEN = 6,        /* one int32 */
     EESD_READ_PAGE_TABLE = 7,    /* ceil(max_seq / kv_page) int32 (-1 = unmapped) */
     EESD_READ_TREE_TOKENS = 8,   /* tree mode: the tokens of the block's 1 + K * tree_width rows as int32 */
-    EESD_READ_CALI_STATE = 9     /* three doubles: theta_hat, the observations behind it, verifications n */
+    EESD_READ_CALI_STATE = 9,    /* three doubles: theta_hat, the observations behind it, verifications n */
+    EESD_READ_VERIFY_PROBS = 10, /* index = verify row i: vocab floats, the probability row the last eesd_accept judged draft i on
+                                    (sampling mode; rows 0..a only: the accept kernel stops at the first rejection) */
+    EESD_READ_LAUNCH_COUNTS = 11 /* 16 int32: weight-streaming product launches since eesd_create, [kernel][epilogue] with kernel
+                                    0 = VALU family, 1 = one workgroup per 16-row tile, 2 = one workgroup per row group,
+                                    3 = tiles sharing the activations through LDS; epilogue 0 LM head, 1 residual, 2 SwiGLU, 3 QKV */
 };
 /* Copies internal state to HOST memory as fp32 / int32.  Synchronises.  n_tokens limits KV reads. */
 int eesd_debug_read(eesd_ctx* ctx, int what, int index, int32_t n_tokens, void* host_dst, size_t bytes);
@@ -268,6 +276,10 @@ int eesd_debug_read(eesd_ctx* ctx, int what, int index, int32_t n_tokens, void* 
 int eesd_debug_force_drafts(eesd_ctx* ctx, const int32_t* toks, int32_t n);
 /* Teacher forcing: replaces the pending token (state must be ready). */
 int eesd_debug_force_pending(eesd_ctx* ctx, int32_t tok);
+/* Teacher forcing: eesd_rollback with ANY 0 <= n_accepted <= K (tree mode: <= the accepted depth) and a pending
+ * token of the caller's choice, so that a test can keep the library on another implementation's token stream.
+ * NOT lossless: never part of decoding. */
+int eesd_debug_rollback(eesd_ctx* ctx, int32_t n_accepted, int32_t pending_tok);
 /* Fills KV rows [0, n_tokens) of every cache with a cheap deterministic pattern and sets
  * kv_len = n_tokens, pending = tok: a stand-in for a prefilled cache in micro-benchmarks. */
 int eesd_debug_fill_cache(eesd_ctx* ctx, int32_t n_tokens, int32_t pending_tok);
@@ -308,6 +320,17 @@ int eesd_op_softmax_sample(const float* logits, float* probs, int32_t vocab, flo
 int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,
                  int32_t dtype, int32_t path, int32_t weight_layout, void* hip_stream);
 
+/* eesd_op_gemm for callers that cannot allocate (code under HIP graph capture, serving loops and harnesses that
+ * forbid hipMalloc): the same product on bf16 weights (MFMA kernel family; W, X, Y, weight_layout as above), but
+ * the bf16 staging rows of the activations live in a fixed 1 MiB device array of this library (per GPU, held until
+ * the process ends) instead of a buffer that eesd_op_gemm grows with hipMalloc.  No allocation of any kind is made.
+ * Limits: 1 <= M <= 16, 128 <= in <= 32768, else EESD_ERANGE; out % 16 == 0, in % 128 == 0 else EESD_EINVAL.
+ * All calls on one GPU share that array, which keeps the last call's contents (nothing in it has to start at zero:
+ * rows >= M are never used): calls that overlap on one GPU - different streams, different threads - race.
+ * Does not synchronise. */
+int eesd_op_gemm_noalloc(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,
+                         int32_t weight_layout, void* hip_stream);
+
 /* Rearranges one bf16 weight matrix (DEVICE, row-major [out_rows][in_dim]) into the tile-major layout
  * the MFMA kernel family streams with contiguous reads (EESD_WEIGHTS_TILED).  The rows are dealt to row
  * groups in units of 4 rows; a group is stored contiguously as blocks of 32 columns, each block holding
@@ -320,17 +343,6 @@ int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out
  * consecutive rows; EESD_PACK_GATE_UP (fused gate|up, out_rows = 2 d_ff): 8 gate rows and their 8 up
  * rows; EESD_PACK_QKV (fused q|k|v; head_dim given): 8 rows of a head and their rotary partners
  * head_dim/2 further.  dst: DEVICE, out_rows * in_dim elements, must not overlap src.
-/* eesd_op_gemm for callers that cannot allocate (code under HIP graph capture, serving loops and harnesses that
- * forbid hipMalloc): the same product on bf16 weights (MFMA kernel family; W, X, Y, weight_layout as above), but
- * the bf16 staging rows of the activations live in a fixed 1 MiB device array of this library (per GPU, held until
- * the process ends) instead of a buffer that eesd_op_gemm grows with hipMalloc.  No allocation of any kind is made.
- * Limits: 1 <= M <= 16, 128 <= in <= 32768, else EESD_ERANGE; out % 16 == 0, in % 128 == 0 else EESD_EINVAL.
- * All calls on one GPU share that array, which keeps the last call's contents (nothing in it has to start at zero:
- * rows >= M are never used): calls that overlap on one GPU - different streams, different threads - race.
- * Does not synchronise. */
-int eesd_op_gemm_noalloc(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,
-                         int32_t weight_layout, void* hip_stream);
-
  * out_rows % 16 == 0 (QKV: % head_dim), in_dim % 128 == 0.  Does not synchronise. */
 int eesd_pack_weight(const void* src, void* dst, int32_t out_rows, int32_t in_dim, int32_t kind, int32_t head_dim,
                      void* hip_stream);

@@ -17,7 +17,7 @@ TS_BETA, TS_FIXED, TS_SCHEDULE, TS_CALI = 0, 1, 2, 3
 WEIGHTS_ROW_MAJOR, WEIGHTS_TILED = 0, 1
 PACK_PLAIN, PACK_GATE_UP, PACK_QKV = 0, 1, 2
 GEMM_AUTO, GEMM_VALU, GEMM_MFMA = 0, 1, 2
-READ_DRAFT_LOGITS, READ_DRAFT_PROBS, READ_VERIFY_LOGITS, READ_KV_K, READ_KV_V, READ_TOKENS, READ_KV_LEN, READ_PAGE_TABLE, READ_TREE_TOKENS, READ_CALI_STATE = range(10)
+READ_DRAFT_LOGITS, READ_DRAFT_PROBS, READ_VERIFY_LOGITS, READ_KV_K, READ_KV_V, READ_TOKENS, READ_KV_LEN, READ_PAGE_TABLE, READ_TREE_TOKENS, READ_CALI_STATE, READ_VERIFY_PROBS, READ_LAUNCH_COUNTS = range(12)
 
 _STATUS = {0: "EESD_OK", -1: "EESD_EINVAL", -2: "EESD_ENOMEM", -3: "EESD_ESTATE", -4: "EESD_ERANGE", -5: "EESD_EDEVICE"}
 
@@ -81,7 +81,7 @@ def lib_path() -> str:
 _LIB = None
 EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_accepted_tokens", "eesd_rollback",
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
-           "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_fill_cache",
+           "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_rollback", "eesd_debug_fill_cache",
            "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_set_calibration", "eesd_cali_score",
            "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm", "eesd_op_gemm_noalloc", "eesd_pack_weight"]
 
@@ -114,6 +114,7 @@ def lib() -> C.CDLL:
     L.eesd_debug_read.argtypes = [VP, C.c_int, C.c_int, I32, VP, C.c_size_t]
     L.eesd_debug_force_drafts.argtypes = [VP, P(I32), I32]
     L.eesd_debug_force_pending.argtypes = [VP, I32]
+    L.eesd_debug_rollback.argtypes = [VP, I32, I32]
     L.eesd_debug_fill_cache.argtypes = [VP, I32, I32]
     L.eesd_set_tunable.argtypes = [C.c_char_p, C.c_int]
     L.eesd_debug_profile_begin.argtypes = [VP, I32, I32, I32]
@@ -131,8 +132,8 @@ def lib() -> C.CDLL:
     L.eesd_op_accept.argtypes = [VP, VP, VP, P(C.c_double), I32, I32, I32, VP, P(I32)]
     L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
     L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, I32, VP]
-    L.eesd_pack_weight.argtypes = [VP, VP, I32, I32, I32, I32, VP]
     L.eesd_op_gemm_noalloc.argtypes = [VP, VP, VP, I32, I32, I32, I32, VP]
+    L.eesd_pack_weight.argtypes = [VP, VP, I32, I32, I32, I32, VP]
     for name in EXPORTS:
         if name not in ("eesd_destroy", "eesd_last_error", "eesd_host_uniform"):
             getattr(L, name).restype = C.c_int
@@ -265,6 +266,10 @@ class EESD:
     def rollback(self, n_accepted: int) -> None:
         self._ck(lib().eesd_rollback(self._h, int(n_accepted)))
 
+    def rollback_forced(self, n_accepted: int, pending: int) -> None:
+        """Test hook (teacher forcing): keep any number of drafts and continue from a token of the caller's choice."""
+        self._ck(lib().eesd_debug_rollback(self._h, int(n_accepted), int(pending)))
+
     def generate(self, prompt, max_new: int):
         p = _i32(prompt)
         out = np.zeros(max_new, np.int32)
@@ -335,6 +340,13 @@ class EESD:
     def verify_logits(self, row: int) -> np.ndarray:
         return self._read(READ_VERIFY_LOGITS, row, 0, np.empty(self.vocab, np.float32))
 
+    def verify_probs(self, row: int) -> np.ndarray:
+        return self._read(READ_VERIFY_PROBS, row, 0, np.empty(self.vocab, np.float32))
+
+    def launch_counts(self) -> np.ndarray:
+        """[kernel][epilogue] launches: kernel 0 VALU, 1 per-tile, 2 per-group, 3 LDS-shared tiles; epilogue 0 head, 1 residual, 2 SwiGLU, 3 QKV."""
+        return self._read(READ_LAUNCH_COUNTS, 0, 0, np.empty(16, np.int32)).reshape(4, 4)
+
     def kv(self, cache: int, n_tokens: int):
         sh = self.shape
         k = self._read(READ_KV_K, cache, n_tokens, np.empty((n_tokens, sh["n_kv_heads"], sh["head_dim"]), np.float32))
@@ -392,6 +404,13 @@ def op_gemm(W, X, Y, path: int = GEMM_AUTO, stream: int = 0, weight_layout: int 
         raise EesdError(rc, "eesd_op_gemm")
 
 
+def op_gemm_noalloc(W, X, Y, stream: int = 0, weight_layout: int = WEIGHTS_ROW_MAJOR) -> None:
+    M, inn = X.shape
+    rc = lib().eesd_op_gemm_noalloc(W.data_ptr(), X.data_ptr(), Y.data_ptr(), M, W.shape[0], inn, weight_layout, C.c_void_p(stream))
+    if rc:
+        raise EesdError(rc, "eesd_op_gemm_noalloc")
+
+
 def pack_weight(W, kind: int = PACK_PLAIN, head_dim: int = 0, stream: int = 0):
     """Tile-major copy of one bf16 matrix [out][in] (same shape and dtype; the library's kernel does the
     rearranging, torch only owns the new buffer)."""
@@ -402,13 +421,6 @@ def pack_weight(W, kind: int = PACK_PLAIN, head_dim: int = 0, stream: int = 0):
     if rc:
         raise EesdError(rc, "eesd_pack_weight")
     return dst
-
-
-def op_gemm_noalloc(W, X, Y, stream: int = 0, weight_layout: int = WEIGHTS_ROW_MAJOR) -> None:
-    M, inn = X.shape
-    rc = lib().eesd_op_gemm_noalloc(W.data_ptr(), X.data_ptr(), Y.data_ptr(), M, W.shape[0], inn, weight_layout, C.c_void_p(stream))
-    if rc:
-        raise EesdError(rc, "eesd_op_gemm_noalloc")
 
 
 def pack_weights(weights: dict) -> dict:

@@ -131,6 +131,7 @@ struct eesd_ctx {
     float *h_t, *cali_u, *theta_dev;      // H_t^(T) [d], W^i H_t^(T) [d], theta_M
     bf16_t* h_tb;                         // bf16 copy of h_t (operand of the MFMA product)
     float* hn_rows;                       // verify_reuse: layer-N hidden state of every draft step's input row [k_cap][d]
+    int launch_counts[16];   // product launches since creation, [kernel 0 VALU / 1 one workgroup per tile / 2 one workgroup per row group / 3 LDS-shared tiles][epilogue]
     int max_splits;
     int n_cu;              // compute units of the device (fixes the row groups of the tile-major weight layout)
     int ssq_slots;         // partial sums of squares a residual product leaves per row
@@ -294,7 +295,10 @@ static hipError_t launch_group(const GemmP& p, hipStream_t st) {
 }
 
 template <int EPI>
-static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
+static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st, int* kernel_taken = nullptr) {
+    int taken_dummy;
+    int& taken = kernel_taken ? *kernel_taken : taken_dummy;
+    taken = 3;
     // Which kernel (measured per product at the 13B and 70B shapes): one workgroup per tile streams
     // fastest for few rows and for the products with few tiles (QKV, attention output, FFN down) at
     // any M <= 16; from 6 rows on (7 for the widest) the products with many tiles (gate/up, LM heads) gain more
@@ -304,7 +308,7 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
     const bool partial = EPI == EPI_RESID && p.y_partial;
     if (p.w_packed && p.n_groups != n_tiles16) {
         // one row group per CU: decoding blocks take the group kernel, prefill blocks the tile kernel with a wave per tile of the group
-        if (p.M <= 16) return launch_group<EPI>(p, st);
+        if (p.M <= 16) { taken = 2; return launch_group<EPI>(p, st); }
         if (p.in_dim % GT_KC_MIN) return hipErrorInvalidValue;
         if (p.M <= 32) return launch_tile_t<EPI, 2, 256, 4>(p, ksplit, st);
         if (p.M <= 64) return launch_tile_t<EPI, 4, 256, 4>(p, ksplit, st);
@@ -333,6 +337,7 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st) {
         return hipErrorInvalidValue;
     }
     if (p.M > 16) return hipErrorInvalidValue;
+    taken = 1;
     const int n_tiles = p.out_rows / 16, steps = p.in_dim / 128;
     int nw = g_nw_epi[EPI] ? g_nw_epi[EPI] : g_mfma_nw;
     if (!nw) {
@@ -390,9 +395,12 @@ static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
         GemmP pm = p;
         pm.w_packed = c->cfg.weight_layout == EESD_WEIGHTS_TILED;
         pm.n_groups = pm.w_packed ? pack_n_groups(pm.out_rows, c->n_cu) : 0;
-        HIP_TRY(c, launch_mfma<EPI>(pm, ksplit, c->stream));
+        int taken = 0;
+        HIP_TRY(c, launch_mfma<EPI>(pm, ksplit, c->stream, &taken));
+        ++c->launch_counts[taken * 4 + EPI];
     } else {
         HIP_TRY(c, launch_valu<EPI>(p, is_bf16(c), c->stream));
+        ++c->launch_counts[EPI];
     }
     if (prof) {
         HIP_TRY(c, hipEventRecord(c->prof_ev[2 * c->prof_used + 1], c->stream));
@@ -954,6 +962,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->sched_round = 0; c->round = 0; c->kv_len = 0; c->n_drafted = 0; c->forced_pos = 0;
     c->prof_family = -1; c->prof_epi = 0; c->prof_in = 0; c->prof_used = 0;
     memset(&c->stats, 0, sizeof c->stats);
+    memset(c->launch_counts, 0, sizeof c->launch_counts);
 
     int rc = EESD_OK;
     auto bail = [&](int code) { std::string e = c->err; eesd_destroy(c); (void)e; return code; };
@@ -1292,13 +1301,9 @@ extern "C" int eesd_accepted_tokens(eesd_ctx* c, int32_t* toks, int32_t cap, int
     return EESD_OK;
 }
 
-extern "C" int eesd_rollback(eesd_ctx* c, int32_t n_accepted) {
-    if (!c) return EESD_EINVAL;
-    if (c->state != ST_ACCEPTED) return fail(c, EESD_ESTATE, "rollback: nothing accepted");
+// keeps n_accepted drafts of the round just judged (the caller has checked n_accepted)
+static int commit_round(eesd_ctx* c, int n_accepted) {
     const int K = c->n_drafted;
-    if (n_accepted < 0 || n_accepted > K) return fail(c, EESD_ERANGE, "rollback: n_accepted %d outside [0,%d]", n_accepted, K);
-    if (tree_width(c) > 1 && n_accepted > c->last_a)
-        return fail(c, EESD_ERANGE, "rollback: tree mode keeps at most the %d accepted nodes", c->last_a);
     // the stream is idle here: eesd_accept synchronised it
     {   // the hidden state whose output is the next pending token: verify row of the last kept node
         int row = n_accepted;
@@ -1318,6 +1323,16 @@ extern "C" int eesd_rollback(eesd_ctx* c, int32_t n_accepted) {
     c->round += 1;
     c->state = ST_READY;
     return EESD_OK;
+}
+
+extern "C" int eesd_rollback(eesd_ctx* c, int32_t n_accepted) {
+    if (!c) return EESD_EINVAL;
+    if (c->state != ST_ACCEPTED) return fail(c, EESD_ESTATE, "rollback: nothing accepted");
+    // keeping more, or fewer, drafts than the accept rule kept would break the equality of the output
+    // distribution with auto-regressive decoding (and the pending token belongs to position last_a)
+    if (n_accepted != c->last_a)
+        return fail(c, EESD_ERANGE, "rollback: n_accepted %d is not the %d drafts eesd_accept kept", n_accepted, c->last_a);
+    return commit_round(c, n_accepted);
 }
 
 extern "C" int eesd_set_calibration(eesd_ctx* c, const eesd_calibration* cal) {
@@ -1373,6 +1388,8 @@ extern "C" int eesd_next_draft_len(eesd_ctx* c, int32_t k_max, int32_t* k_out) {
     *k_out = draw_k(c, std::min((int)k_max, (int)c->cfg.k_cap));
     return EESD_OK;
 }
+
+extern "C" int eesd_debug_force_pending(eesd_ctx* c, int32_t tok);
 
 static double ms_between(hipEvent_t a, hipEvent_t b) {
     float ms = 0.f;
@@ -1454,6 +1471,18 @@ extern "C" int eesd_debug_force_drafts(eesd_ctx* c, const int32_t* toks, int32_t
     return EESD_OK;
 }
 
+extern "C" int eesd_debug_rollback(eesd_ctx* c, int32_t n_accepted, int32_t pending_tok) {
+    if (!c) return EESD_EINVAL;
+    if (c->state != ST_ACCEPTED) return fail(c, EESD_ESTATE, "debug_rollback: nothing accepted");
+    if (n_accepted < 0 || n_accepted > c->n_drafted) return fail(c, EESD_ERANGE, "debug_rollback: n_accepted %d outside [0,%d]", n_accepted, c->n_drafted);
+    if (tree_width(c) > 1 && n_accepted > c->last_a)
+        return fail(c, EESD_ERANGE, "debug_rollback: tree mode keeps at most the %d accepted nodes", c->last_a);
+    if (pending_tok < 0 || pending_tok >= c->cfg.vocab) return fail(c, EESD_EINVAL, "debug_rollback: token out of range");
+    int rc = commit_round(c, n_accepted);
+    if (rc) return rc;
+    return eesd_debug_force_pending(c, pending_tok);
+}
+
 extern "C" int eesd_debug_force_pending(eesd_ctx* c, int32_t tok) {
     if (!c) return EESD_EINVAL;
     if (c->state != ST_READY || c->n_drafted != 0) return fail(c, EESD_ESTATE, "force_pending: state is not ready");
@@ -1531,6 +1560,16 @@ extern "C" int eesd_debug_read(eesd_ctx* c, int what, int index, int32_t n_token
         case EESD_READ_VERIFY_LOGITS: {
             if (index < 0 || index >= MAX_ROWS || bytes < row) return fail(c, EESD_ERANGE, "debug_read: bad verify row or size");
             HIP_TRY(c, hipMemcpy(host_dst, c->logits + (size_t)index * g.vocab, row, hipMemcpyDeviceToHost));
+            return EESD_OK;
+        }
+        case EESD_READ_VERIFY_PROBS: {
+            if (index < 0 || index >= MAX_ROWS || bytes < row) return fail(c, EESD_ERANGE, "debug_read: bad verify row or size");
+            HIP_TRY(c, hipMemcpy(host_dst, c->p_rows + (size_t)index * g.vocab, row, hipMemcpyDeviceToHost));
+            return EESD_OK;
+        }
+        case EESD_READ_LAUNCH_COUNTS: {
+            if (bytes < sizeof c->launch_counts) return fail(c, EESD_ERANGE, "debug_read: destination too small");
+            memcpy(host_dst, c->launch_counts, sizeof c->launch_counts);
             return EESD_OK;
         }
         case EESD_READ_KV_K:

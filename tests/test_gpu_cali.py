@@ -53,8 +53,7 @@ def test_predictor_scores_match_oracle_under_teacher_forcing(name, temp, tiled):
         h_t = o.h_target_rows[a]
         cali.update(a, K)
         o.rollback(a, y)
-        g.rollback(a)
-        g.force_pending(y)
+        g.rollback_forced(a, y)
         th, w, n = g.cali_state()
         assert (th, w, n) == (cali.theta_hat, cali.weight, cali.n)
     assert max(seen) - min(seen) > 0.05

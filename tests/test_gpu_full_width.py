@@ -32,28 +32,74 @@ def _round_parity(o, g, ks, tol):
         a, y = o.accept()
         g.accept()
         o.rollback(a, y)
-        g.rollback(a)
-        g.force_pending(y)
+        g.rollback_forced(a, y)
 
 
-@pytest.mark.parametrize("name,n_prompt,ks,tiled", [("13b", 150, (10, 3), 0), ("70b", 40, (7,), 0), ("13b", 150, (10, 3), 1), ("70b", 140, (7, 2), 1)])
+@pytest.mark.parametrize("name,n_prompt,ks,tiled", [("13b", 150, (10, 3), 0), ("70b", 40, (7,), 0), ("13b", 150, (10, 3), 1), ("70b", 140, (7, 2), 1),
+                                                    ("70b", 140, (10, 15), 1)])
 def test_full_width_reduced_depth_matches_oracle(name, n_prompt, ks, tiled):
-    """tiled = 1: the weights in the tile-major layout the benchmark runs with."""
+    """tiled = 1: the weights in the tile-major layout the benchmark runs with.  The last case is the block of
+    11 and 16 rows on the 70B shape, where the gate/up product and the LM head leave the one-workgroup-per-tile
+    kernel for the one whose tiles share the activations through LDS (8 and 4 tiles per workgroup); the launch
+    counters prove which kernels really ran."""
     require_gpu()
     base = si.LLAMA13B if name == "13b" else si.LLAMA70B
     shape = si.reduced_depth(base, 2, 1)
-    o, g = make_pair(shape, 21, n_prompt + 64, 1.0, k_cap=10, jitter=0.05, gen_device="cuda", kv_page=64, weight_layout=tiled)
+    o, g = make_pair(shape, 21, n_prompt + 64, 1.0, k_cap=max(10, max(ks)), jitter=0.05, gen_device="cuda", kv_page=64, weight_layout=tiled)
     prompt = si.make_prompt(n_prompt, shape["vocab"], 3)
     t_ref = o.prefill(prompt)          # 128-row tiled block + ragged block on the GPU side
     g.prefill(prompt)
     assert rel_err(g.verify_logits(0), o.prefill_logits) < TOL_BF16
     g.force_pending(t_ref)
+    before = g.launch_counts()
     _round_parity(o, g, ks, TOL_BF16)
     n = o.kv_len
     for cache in range(3):
         ref = o.kv[cache] if cache < 2 else o.ee_kv
         k, v = g.kv(cache, n)
         assert rel_err(k, ref.k[:n]) < TOL_BF16 and rel_err(v, ref.v[:n]) < TOL_BF16
+    if tiled:
+        # [kernel][epilogue] launches of the rounds: QKV and both residual products of every pass run one workgroup per
+        # row group (kernel 2); gate/up and the heads one workgroup per tile (1) or, for many rows, LDS-shared tiles (3)
+        d = g.launch_counts() - before
+        steps, L = sum(ks), shape["n_layers"]
+        assert d[2][3] == 2 * steps + len(ks) * (L + 1) and d[2][1] == 2 * (2 * steps + len(ks) * L)
+        assert d[0].sum() == 0 and d[1][1] == 0 and d[1][3] == 0 and d[3][1] == 0 and d[3][3] == 0
+        if name == "70b":
+            big = sum(1 for K in ks if K + 1 >= 10)       # verify blocks whose gate/up product shares activations through LDS
+            assert d[3][2] == big * L and d[1][2] == 2 * steps + (len(ks) - big) * L
+            assert d[3][0] == sum(1 for K in ks if K + 1 >= 7) and d[1][0] + d[3][0] == steps + len(ks)
+
+
+def _inject_cache(o, g, n, pending):
+    """The GPU's cache rows (a cheap deterministic pattern) become the oracle's: input data for both sides."""
+    for cache in range(o.L + 1):
+        dst = o.kv[cache] if cache < o.L else o.ee_kv
+        k, v = g.kv(cache, n)
+        dst.k[:n] = k
+        dst.v[:n] = v
+    o.kv_len, o.pending, o.rnd = n, int(pending), 1
+    o.drafts, o.q_rows, o.q_logits = [], [], []
+
+
+@pytest.mark.parametrize("name,n_cache,ks", [("13b", 4080, (10,)), ("70b", 2048, (0, 1, 3, 7, 15))])
+def test_full_width_long_cache_matches_oracle(name, n_cache, ks):
+    """Attention at full width over a long cache without paying for an oracle prefill: the cache is filled with a
+    pattern, read back and given to the oracle as ITS cache; then teacher-forced rounds.  13B shape: 40 heads over
+    4080 + 11 keys (the long-context configuration: many key splits, 64-key steps, the split merge); 70B shape:
+    8 KV heads x 8 query heads over 2048 keys with verify blocks of 1, 2, 4, 8 and 16 rows."""
+    require_gpu()
+    base = si.LLAMA13B if name == "13b" else si.LLAMA70B
+    shape = si.reduced_depth(base, 2, 1)
+    o, g = make_pair(shape, 23, n_cache + 64, 1.0, k_cap=15, jitter=0.05, gen_device="cuda", kv_page=64, weight_layout=1)
+    g.fill_cache(n_cache, 7)
+    _inject_cache(o, g, n_cache, 7)
+    _round_parity(o, g, ks, TOL_BF16)
+    n = o.kv_len
+    for cache in range(3):
+        ref = o.kv[cache] if cache < 2 else o.ee_kv
+        k, v = g.kv(cache, n)
+        assert rel_err(k[n_cache:], ref.k[n_cache:n]) < TOL_BF16 and rel_err(v[n_cache:], ref.v[n_cache:n]) < TOL_BF16
 
 
 @pytest.mark.parametrize("name,width,K", [("13b", 2, 4), ("70b", 3, 5)])
@@ -113,9 +159,7 @@ def test_full_depth_70b_properties():
         g2.verify()
         assert rel_err(g2.verify_logits(0), rows[i].astype(np.float64)) < 2 * TOL_BF16, i
         g2.accept()
-        g2.rollback(0)
-        if i + 1 < len(block):
-            g2.force_pending(block[i + 1])
+        g2.rollback_forced(0, block[min(i + 1, len(block) - 1)])
     # g1: accept whatever the target says, roll back, and compare the caches with g2's
     a, y = g1.accept()
     g1.rollback(a)

@@ -71,13 +71,67 @@ def test_teacher_forced_rounds_match_oracle(name, temp, reuse):
         if safe:
             assert (a_gpu, y_gpu) == (a_ref, y_ref), (K, a_gpu, y_gpu, a_ref, y_ref)
         o.rollback(a_ref, y_ref)
-        g.rollback(a_ref)
-        g.force_pending(y_ref)
+        g.rollback_forced(a_ref, y_ref)
         assert g.kv_len() == o.kv_len == base + a_ref + 1
         _check_caches(o, g, o.kv_len, tol)
     s = g.stats()
     assert (s.rounds, s.drafted, s.accepted) == (o.stats.rounds, o.stats.drafted, o.stats.accepted)
     assert (s.alpha, s.beta) == (o.ts.alpha, o.ts.beta)
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+@pytest.mark.parametrize("temp", [0.0, 1.0])
+def test_gpu_decisions_follow_the_rule_on_the_gpus_own_rows(name, temp):
+    """Every integer a round decides - each draft token, the number of accepted drafts, the next token -
+    must be exactly what the decision rule gives on the probability (greedy: logit) rows the GPU itself
+    produced, with the same uniforms: no margin, no skip.  The GPU runs free (its own draft tokens, its own
+    accept decision inside the round's fused kernels); the oracle is forced along the GPU's tokens, so the
+    logits of both sides stay comparable as well."""
+    require_gpu()
+    shape = SHAPES[name]
+    tol = tol_of(shape)
+    V = shape["vocab"]
+    o, g = make_pair(shape, 5, 160, temp, k_cap=5, gamma=0.05 if temp == 0.0 else None, seed=9)
+    prompt = si.make_prompt(29, V, 2)
+    o.prefill(prompt)
+    t = g.prefill(prompt)
+    if temp > 0:
+        assert orc.decide_sample(g.verify_probs(0), orc.uniform(9, orc.STREAM_RESAMPLE, 0)) == t
+    else:
+        assert orc.argmax_lowest(g.verify_logits(0)) == t
+    o.pending = t
+    n_accepted = 0
+    for K in (3, 5, 1, 4, 5, 2, 5, 0):
+        ds = []
+        for i in range(K):
+            d = g.draft_step()
+            if temp > 0:
+                assert orc.decide_sample(g.draft_probs(i), orc.uniform(9, orc.STREAM_DRAFT, o.rnd, i)) == d, ("draft token", K, i)
+            else:
+                assert orc.argmax_lowest(g.draft_logits(i)) == d, ("draft token", K, i)
+            o.draft_step(force_token=d)
+            assert rel_err(g.draft_logits(i), o.q_logits[i]) < tol, ("draft logits", K, i)
+            ds.append(d)
+        pl = o.verify()
+        g.verify()
+        a, y = g.accept()
+        if temp > 0:
+            p = np.full((K + 1, V), np.nan, np.float32)      # the accept kernel stops at the first rejection: rows past a do not exist
+            for i in range(a + 1):
+                p[i] = g.verify_probs(i)
+            q = np.stack([g.draft_probs(i) for i in range(K)]) if K else None
+            us = [orc.uniform(9, orc.STREAM_ACCEPT, o.rnd, i) for i in range(K)]
+            assert orc.decide_accept(p, q, ds, us, orc.uniform(9, orc.STREAM_RESAMPLE, o.rnd), False) == (a, y), ("accept", K)
+        else:
+            p = np.stack([g.verify_logits(i) for i in range(K + 1)])
+            assert orc.decide_accept(p, None, ds, [], 0.0, True) == (a, y), ("accept", K)
+        for i in range(K + 1):
+            assert rel_err(g.verify_logits(i), pl[i]) < tol, ("verify logits", K, i)
+        n_accepted += a
+        o.rollback(a, y)
+        g.rollback(a)
+        _check_caches(o, g, o.kv_len, tol)
+    assert n_accepted > 0      # both branches of the rule were taken
 
 
 @pytest.mark.parametrize("path,ksplit", [("valu", 0), ("mfma", 1), ("mfma", 2), ("mfma", 8), ("auto", 4), ("tile", 0), ("tile", 2), ("nofuse", 0), ("nofuse", 4), ("tile_nofuse", 2), ("fuse", 0), ("tile_fuse", 0), ("fuse_wo", 0), ("fuse_down", 4)])
@@ -113,8 +167,7 @@ def test_kernel_families_and_k_splits_match_oracle(path, ksplit):
             a, y = o.accept()
             g.accept()
             o.rollback(a, y)
-            g.rollback(a)
-            g.force_pending(y)
+            g.rollback_forced(a, y)
         _check_caches(o, g, o.kv_len, tol)
     finally:
         pk.set_tunable("mfma_ksplit", 0)
@@ -147,8 +200,7 @@ def test_long_context_round_matches_oracle(name, n_prompt):
         a, y = o.accept()
         g.accept()
         o.rollback(a, y)
-        g.rollback(a)
-        g.force_pending(y)
+        g.rollback_forced(a, y)
     _check_caches(o, g, o.kv_len, tol)
 
 
@@ -174,9 +226,7 @@ def test_verify_block_equals_sequential_steps_on_gpu(name):
         row = g2.verify_logits(0)
         assert rel_err(row, rows[i].astype(np.float64)) < 2 * tol
         g2.accept()
-        g2.rollback(0)
-        if i + 1 < len(block):
-            g2.force_pending(block[i + 1])
+        g2.rollback_forced(0, block[min(i + 1, len(block) - 1)])
     n = 26
     for cache in range(shape["n_layers"] + 1):
         k1, v1 = g1.kv(cache, n)
@@ -208,8 +258,20 @@ def test_generate_matches_oracle_stream(name, temp, mode):
         for tr in trace:
             n_commit = tr["a"] + 1
             if pos + n_commit > first:
-                gaps = [top2_gap(tr["p_logits"][i]) for i in range(tr["a"] + 1)] + [top2_gap(q) for q in tr["q_logits"]]
-                ok = temp > 0 or min(gaps) < 4 * tol
+                if temp == 0.0:
+                    gaps = [top2_gap(tr["p_logits"][i]) for i in range(tr["a"] + 1)] + [top2_gap(q) for q in tr["q_logits"]]
+                    ok = min(gaps) < 4 * tol
+                else:
+                    # every draw and every accept test of that round, with the oracle's rows: one of them must be a near-tie
+                    rnd, K, a, ds = trace.index(tr) + 1, tr["K"], tr["a"], tr["drafts"]
+                    qs = [o._probs(q) for q in tr["q_logits"]]
+                    ps = o._probs(tr["p_logits"])
+                    margins = [sample_margin(qs[i], orc.uniform(4, orc.STREAM_DRAFT, rnd, i)) for i in range(K)]
+                    margins += [abs(orc.uniform(4, orc.STREAM_ACCEPT, rnd, i) * float(qs[i][ds[i]]) - float(ps[i][ds[i]])) / max(1e-30, float(ps[i][ds[i]]))
+                                for i in range(min(K, a + 1))]
+                    r = ps[a] if a == K else np.maximum(np.float32(0), ps[a] - qs[a])
+                    margins.append(sample_margin(r, orc.uniform(4, orc.STREAM_RESAMPLE, rnd)))
+                    ok = min(margins) < 5 * tol
                 break
             pos += n_commit
         assert ok, f"streams differ at {first} with a clear margin"
@@ -255,7 +317,7 @@ def test_heads_of_64_channels_bf16_match_oracle(tiled, tree):
                     assert rel_err(g.verify_logits(1 + (i - 1) * tree + j), o.tree_logits[(i, j)]) < tol, ("node", K, i, j)
             g.accept()
             o.rollback_tree(0, y, [])
-            g.rollback(0)
+            g.rollback_forced(0, y)
         else:
             pl = o.verify()
             for i in range(K + 1):
@@ -263,8 +325,7 @@ def test_heads_of_64_channels_bf16_match_oracle(tiled, tree):
             a, y = o.accept()
             g.accept()
             o.rollback(a, y)
-            g.rollback(a)
-        g.force_pending(y)
+            g.rollback_forced(a, y)
     _check_caches(o, g, o.kv_len, tol)
 
 
@@ -317,8 +378,7 @@ def test_verify_with_reused_hidden_states_equals_full_verify(name):
         a, y = g0.accept()
         g1.accept()
         g0.rollback(a)
-        g1.rollback(a)
-        g1.force_pending(y)
+        g1.rollback_forced(a, y)
     n = g0.kv_len()
     for cache in range(shape["n_layers"] + 1):
         k0, v0 = g0.kv(cache, n)
@@ -403,9 +463,11 @@ def test_call_order_and_range_errors():
         g.rollback(0)
     assert e.value.code == -3
     a, y = g.accept()
-    with pytest.raises(pk.EesdError) as e:
-        g.rollback(4)
-    assert e.value.code == -4
+    for wrong in (4, a + 1, a - 1):         # only the a that eesd_accept returned may be kept
+        if wrong != a:
+            with pytest.raises(pk.EesdError) as e:
+                g.rollback(wrong)
+            assert e.value.code == -4
     g.rollback(a)
     with pytest.raises(pk.EesdError) as e:
         g.generate([1] * 40, 30)
@@ -493,7 +555,7 @@ def test_edge_sizes(name):
     a, y = o.accept()
     g.accept()
     o.rollback(a, y)
-    g.rollback(a)
+    g.rollback_forced(a, y)
     # single new token / exact fit of max_seq
     _, g2 = make_pair(shape, 17, 64, 0.0, k_cap=3)
     out, st = g2.generate(si.make_prompt(10, shape["vocab"], 1), 1)

@@ -62,14 +62,12 @@ def test_teacher_forced_tree_rounds_match_oracle(name, width):
             leaf += a_ref > 0 and branch[-1] != 0
             full += a_ref == K
             o.rollback_tree(a_ref, y_ref, branch)
-            g.rollback(a_ref)
-            g.force_pending(y_ref)
+            g.rollback_forced(a_ref, y_ref)
             assert g.kv_len() == o.kv_len == base + a_ref + 1
             _check_caches(o, g, o.kv_len, tol)
         else:   # a near-tie: keep the two sides on the same text without using the GPU's decision
             o.rollback_tree(0, y_ref, [])
-            g.rollback(0)
-            g.force_pending(y_ref)
+            g.rollback_forced(0, y_ref)
     assert leaf + full > 0
     s = g.stats()
     assert (s.rounds, s.drafted, s.accepted) == (o.stats.rounds, o.stats.drafted, o.stats.accepted)
