@@ -89,6 +89,9 @@ typedef struct eesd_config {
                                 result up to rounding; ignored in tree mode */
     int32_t weight_layout;   /* EESD_WEIGHTS_ROW_MAJOR, or EESD_WEIGHTS_TILED: every matrix except tok_emb and the norm gains
                                 was rearranged by eesd_pack_weight (bf16 models, MFMA kernel family only) */
+    int32_t logits_bf16;     /* 1: both LM heads store their logits as bf16 (rounded to nearest even from the fp32 sums) and the
+                                softmax / sampling / accept kernels read those; probabilities stay fp32.  bf16 models, MFMA
+                                kernel family only.  0: fp32 logits */
 } eesd_config;
 
 /* One decoder layer.  Every matrix is row-major [out][in] in the configured dtype. */
@@ -309,6 +312,13 @@ int eesd_set_tunable(const char* name, int value);
  * drafts: DEVICE int32 [K]; uniforms: HOST double [K+1]; result: HOST int32[2] = {a, y}. */
 int eesd_op_accept(const float* p_rows, const float* q_rows, const int32_t* drafts, const double* uniforms,
                    int32_t K, int32_t vocab, int32_t greedy, void* hip_stream, int32_t* result);
+/* The verification tail as eesd_accept runs it, on given logit rows: p_logits DEVICE [K+1][vocab], fp32 or (logits_bf16 = 1)
+ * bf16; row i becomes softmax(p_logits[i] / temperature) in p_rows[i] (DEVICE fp32 [K+1][vocab], rows 0..a only: the walk
+ * stops at the first rejection), draft i is accepted iff u_i q_i(d_i) < p_i(d_i), the first rejected position is resampled
+ * from norm(max(0, p - q)), K acceptances draw the bonus token from row K.  temperature 0: greedy on the logits, p_rows,
+ * q_rows and uniforms unused.  q_rows, drafts, uniforms, result as eesd_op_accept. */
+int eesd_op_accept_logits(const void* p_logits, int32_t logits_bf16, float* p_rows, const float* q_rows, const int32_t* drafts,
+                          const double* uniforms, int32_t K, int32_t vocab, float temperature, void* hip_stream, int32_t* result);
 /* softmax(logits / temperature) of one DEVICE fp32 row into probs (DEVICE fp32), then an
  * inverse-CDF draw with u (temperature 0: argmax, probs untouched).  *token: HOST. */
 int eesd_op_softmax_sample(const float* logits, float* probs, int32_t vocab, float temperature, double u,

@@ -34,7 +34,8 @@ class _Config(C.Structure):
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_seq", C.c_int32),
                 ("kv_page", C.c_int32), ("k_cap", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
                 ("ts_alpha0", C.c_double), ("ts_beta0", C.c_double), ("ts_mode", C.c_int32), ("ts_update", C.c_int32),
-                ("gemm_path", C.c_int32), ("tree_width", C.c_int32), ("verify_reuse", C.c_int32), ("weight_layout", C.c_int32)]
+                ("gemm_path", C.c_int32), ("tree_width", C.c_int32), ("verify_reuse", C.c_int32), ("weight_layout", C.c_int32),
+                ("logits_bf16", C.c_int32)]
 
 
 class _Calibration(C.Structure):
@@ -83,7 +84,7 @@ EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "ee
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_rollback", "eesd_debug_fill_cache",
            "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_set_calibration", "eesd_cali_score",
-           "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_softmax_sample", "eesd_op_gemm", "eesd_op_gemm_noalloc", "eesd_pack_weight"]
+           "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_accept_logits", "eesd_op_softmax_sample", "eesd_op_gemm", "eesd_op_gemm_noalloc", "eesd_pack_weight"]
 
 
 def lib() -> C.CDLL:
@@ -130,6 +131,7 @@ def lib() -> C.CDLL:
                                         P(C.c_double), P(I32)]
     L.eesd_host_cali_update.argtypes = [P(C.c_double), P(C.c_double), P(C.c_int64), I32, I32, I32]
     L.eesd_op_accept.argtypes = [VP, VP, VP, P(C.c_double), I32, I32, I32, VP, P(I32)]
+    L.eesd_op_accept_logits.argtypes = [VP, I32, VP, VP, VP, P(C.c_double), I32, I32, C.c_float, VP, P(I32)]
     L.eesd_op_softmax_sample.argtypes = [VP, VP, I32, C.c_float, C.c_double, VP, P(I32)]
     L.eesd_op_gemm.argtypes = [VP, VP, VP, I32, I32, I32, I32, I32, I32, VP]
     L.eesd_op_gemm_noalloc.argtypes = [VP, VP, VP, I32, I32, I32, I32, VP]
@@ -196,14 +198,16 @@ class EESD:
 
     def __init__(self, weights: dict, max_seq: int, temperature: float, seed: int = 0, k_cap: int = 10,
                  kv_page: int = 16, alpha0: float = 1.0, beta0: float = 1.0, ts_mode: int = TS_BETA,
-                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0, tree_width: int = 0, verify_reuse: int = 0, weight_layout: int = WEIGHTS_ROW_MAJOR):
+                 ts_update: int = 0, gemm_path: int = GEMM_AUTO, stream: int = 0, tree_width: int = 0, verify_reuse: int = 0, weight_layout: int = WEIGHTS_ROW_MAJOR,
+                 logits_bf16: int = 0):
         sh = weights["shape"]
         self._keep = weights
         self.shape = sh
         self.vocab = sh["vocab"]
         cfg = _Config(sh["n_layers"], sh["n_draft_layers"], sh["d_model"], sh["n_heads"], sh["n_kv_heads"], sh["head_dim"],
                       sh["d_ff"], sh["vocab"], sh["rms_eps"], sh["rope_base"], DTYPE_BF16 if sh["dtype"] == "bf16" else DTYPE_F32,
-                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, tree_width, verify_reuse, weight_layout)
+                      max_seq, kv_page, k_cap, temperature, seed, alpha0, beta0, ts_mode, ts_update, gemm_path, tree_width, verify_reuse, weight_layout,
+                      logits_bf16)
 
         def lw(d):
             return _Layer(*[d[k].data_ptr() for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
@@ -376,6 +380,21 @@ def op_accept(p_rows, q_rows, drafts, uniforms, greedy: bool, stream: int = 0):
                               _ptr(u, C.c_double), K, V, int(greedy), C.c_void_p(stream), _ptr(res, C.c_int32))
     if rc:
         raise EesdError(rc, "eesd_op_accept")
+    return int(res[0]), int(res[1])
+
+
+def op_accept_logits(p_logits, p_rows, q_rows, drafts, uniforms, temperature: float, stream: int = 0):
+    """p_logits: [K+1][V] fp32 or bfloat16 torch tensor on the GPU; p_rows: fp32 [K+1][V] output (None when greedy)."""
+    import torch
+    K = int(drafts.numel())
+    V = int(p_logits.shape[-1])
+    res = np.zeros(2, np.int32)
+    u = np.ascontiguousarray(np.asarray(uniforms if uniforms is not None else np.zeros(K + 1), dtype=np.float64))
+    rc = lib().eesd_op_accept_logits(p_logits.data_ptr(), int(p_logits.dtype == torch.bfloat16), p_rows.data_ptr() if p_rows is not None else None,
+                                     q_rows.data_ptr() if q_rows is not None else None, drafts.data_ptr(), _ptr(u, C.c_double), K, V,
+                                     float(temperature), C.c_void_p(stream), _ptr(res, C.c_int32))
+    if rc:
+        raise EesdError(rc, "eesd_op_accept_logits")
     return int(res[0]), int(res[1])
 
 

@@ -161,6 +161,9 @@ static int fail(eesd_ctx* c, int code, const char* fmt, ...) {
     } while (0)
 
 static inline bool is_bf16(const eesd_ctx* c) { return c->cfg.dtype == EESD_DTYPE_BF16; }
+// logits rows are fp32, or bf16 when the configuration asks the LM heads for bf16 logits
+static inline bool lb16(const eesd_ctx* c) { return c->cfg.logits_bf16 == 1; }
+static inline void* logit_row(const eesd_ctx* c, float* base, size_t row) { return (char*)base + row * (size_t)c->cfg.vocab * (lb16(c) ? 2 : 4); }
 
 static KVView kv_view(const eesd_ctx* c, int cache) {
     KVView v;
@@ -373,6 +376,7 @@ static bool mfma_shape_ok(int out, int in, int epi, int head_dim) {
 static bool pick_mfma(const eesd_ctx* c, int M) {
     if (!is_bf16(c)) return false;
     if (c->cfg.gemm_path == EESD_GEMM_VALU) return false;
+    if (lb16(c)) return true;     // only the MFMA family writes bf16 logits
     if (c->cfg.gemm_path == EESD_GEMM_MFMA || c->cfg.weight_layout == EESD_WEIGHTS_TILED) return true;
     return M >= g_mfma_min_m;
 }
@@ -629,13 +633,13 @@ static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
 
 // logits[m][:] = RMSNorm(x[m]; norm) head^T for rows x0 .. x0+M-1 of c->x.
 // MFMA family: the normalised rows are already in c->xb.
-static int run_head(eesd_ctx* c, const void* norm, const void* head, int x0, int M, float* logits, bool mfma) {
+static int run_head(eesd_ctx* c, const void* norm, const void* head, int x0, int M, void* logits, bool mfma) {
     const eesd_config& g = c->cfg;
     const int d = g.d_model;
     int rc;
     if (mfma) {
         GemmP p = gemm_base(head, c->xb + (size_t)x0 * d, d, M, g.vocab, d);
-        p.Y = logits; p.ldy = g.vocab;
+        p.Y = logits; p.ldy = g.vocab; p.y_bf16 = lb16(c);
         take_xb(c, p);
         if (p.ssq_in) p.ssq_in += (size_t)x0 * p.ssq_tiles;   // partial sums are [row][tile]
         if ((rc = gemm_launch<EPI_PLAIN>(c, true, p))) return rc;
@@ -912,6 +916,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if (g.ts_mode < 0 || g.ts_mode > 3 || g.ts_update < 0 || g.ts_update > 1 || g.gemm_path < 0 || g.gemm_path > 2) return EESD_EINVAL;
     if (g.tree_width < 0 || g.tree_width > TREE_MAX_WIDTH) return EESD_EINVAL;
     if (g.verify_reuse < 0 || g.verify_reuse > 1) return EESD_EINVAL;
+    if (g.logits_bf16 < 0 || g.logits_bf16 > 1 || (g.logits_bf16 == 1 && (g.dtype != EESD_DTYPE_BF16 || g.gemm_path == EESD_GEMM_VALU))) return EESD_EINVAL;
     if (g.weight_layout != EESD_WEIGHTS_ROW_MAJOR && g.weight_layout != EESD_WEIGHTS_TILED) return EESD_EINVAL;
     if (g.weight_layout == EESD_WEIGHTS_TILED && (g.dtype != EESD_DTYPE_BF16 || g.gemm_path == EESD_GEMM_VALU)) return EESD_EINVAL;
     if (g.tree_width >= 2 && (g.temperature != 0.0f || 1 + g.k_cap * g.tree_width > MAX_ROWS)) return EESD_EINVAL;
@@ -1089,6 +1094,23 @@ static int tree_width(const eesd_ctx* c) { return c->cfg.tree_width >= 2 ? c->cf
 // most rows a verify block can have
 static int rows_cap(const eesd_ctx* c) { return 1 + c->cfg.k_cap * tree_width(c); }
 
+// softmax(row / T) -> probs, draw with u (greedy: argmax); the row is fp32 or bf16 logits
+static hipError_t launch_softmax_sample(eesd_ctx* c, const void* row, float* probs, double u, int forced, int32_t* tok_out) {
+    const int V = c->cfg.vocab;
+    if (lb16(c)) {
+        hipError_t e = smp_allow(softmax_sample_kernel<bf16_t>, V);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(softmax_sample_kernel<bf16_t>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(V), c->stream, (const bf16_t*)row, probs, V,
+                           inv_temperature(c), greedy(c), u, forced, tok_out, smp_use_lds(V));
+    } else {
+        hipError_t e = smp_allow(softmax_sample_kernel<float>, V);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(softmax_sample_kernel<float>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(V), c->stream, (const float*)row, probs, V,
+                           inv_temperature(c), greedy(c), u, forced, tok_out, smp_use_lds(V));
+    }
+    return hipGetLastError();
+}
+
 static void reset_sequence(eesd_ctx* c) {
     release_pages(c, 0);
     c->kv_len = 0; c->n_drafted = 0; c->round = 0; c->sched_round = 0;
@@ -1126,9 +1148,7 @@ extern "C" int eesd_prefill(eesd_ctx* c, const int32_t* prompt, int32_t n, int32
     rc = run_head(c, c->w.final_norm, c->w.lm_head, last_m - 1, 1, c->logits, last_mfma);
     if (rc) return rc;
     double u = uniform53(g.seed, STREAM_RESAMPLE, 0, 0, 0);
-    HIP_TRY(c, smp_allow(softmax_sample_kernel, g.vocab));
-    hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, c->logits, c->p_rows, g.vocab,
-                       inv_temperature(c), greedy(c), u, -1, c->blk_tok, smp_use_lds(g.vocab));
+    HIP_TRY(c, launch_softmax_sample(c, c->logits, c->p_rows, u, -1, c->blk_tok));
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipMemcpyAsync(c->h_result, c->blk_tok, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1164,7 +1184,7 @@ extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
         HIP_TRY(c, hipGetLastError());
     }
     if ((rc = run_layer(c, c->w.ee_layer, g.n_layers, 1, pos, mfma, c->w.ee_norm))) return rc;
-    float* ql = c->q_logits + (size_t)i * g.vocab;
+    void* ql = logit_row(c, c->q_logits, i);
     if ((rc = run_head(c, c->w.ee_norm, c->w.ee_head, 0, 1, ql, mfma))) return rc;
     const int width = tree_width(c);
     if (width > 1) {
@@ -1175,16 +1195,15 @@ extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
             for (int j = 0; j < width; ++j) tf.tok[j] = c->forced[c->forced_pos + j];
             c->forced_pos += width;
         }
-        hipLaunchKernelGGL(top_candidates_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, ql, g.vocab, width, tf,
-                           c->tree_blk + 1 + i * width, c->blk_tok + i + 1);
+        if (lb16(c)) hipLaunchKernelGGL(top_candidates_kernel<bf16_t>, dim3(1), dim3(SMP_THREADS), 0, c->stream, (const bf16_t*)ql, g.vocab, width, tf,
+                                        c->tree_blk + 1 + i * width, c->blk_tok + i + 1);
+        else hipLaunchKernelGGL(top_candidates_kernel<float>, dim3(1), dim3(SMP_THREADS), 0, c->stream, (const float*)ql, g.vocab, width, tf,
+                                c->tree_blk + 1 + i * width, c->blk_tok + i + 1);
     } else {
         int forced = -1;
         if (c->forced_pos < c->forced.size()) forced = c->forced[c->forced_pos++];
         double u = uniform53(g.seed, STREAM_DRAFT, c->round, i, 0);
-        HIP_TRY(c, smp_allow(softmax_sample_kernel, g.vocab));
-        hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, ql,
-                           c->q_rows + (size_t)i * g.vocab, g.vocab, inv_temperature(c), greedy(c), u, forced, c->blk_tok + i + 1,
-                           smp_use_lds(g.vocab));
+        HIP_TRY(c, launch_softmax_sample(c, ql, c->q_rows + (size_t)i * g.vocab, u, forced, c->blk_tok + i + 1));
     }
     HIP_TRY(c, hipGetLastError());
     c->n_drafted = i + 1;
@@ -1240,8 +1259,10 @@ extern "C" int eesd_verify(eesd_ctx* c) {
 static int accept_tree(eesd_ctx* c, int32_t* n_accepted, int32_t* next_token) {
     const eesd_config& g = c->cfg;
     const int K = c->n_drafted, width = tree_width(c), M = 1 + K * width;
-    hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(SMP_THREADS), 0, c->stream, c->logits, c->tree_blk, K, width, g.vocab, c->result_dev,
-                       c->blk_tok);
+    if (lb16(c)) hipLaunchKernelGGL(accept_tree_kernel<bf16_t>, dim3(1), dim3(SMP_THREADS), 0, c->stream, (const bf16_t*)c->logits, c->tree_blk, K, width, g.vocab,
+                                    c->result_dev, c->blk_tok);
+    else hipLaunchKernelGGL(accept_tree_kernel<float>, dim3(1), dim3(SMP_THREADS), 0, c->stream, (const float*)c->logits, c->tree_blk, K, width, g.vocab,
+                            c->result_dev, c->blk_tok);
     HIP_TRY(c, hipGetLastError());
     const int per = c->n_caches * g.n_kv_heads * g.head_dim;
     KVView v = kv_view(c, 0);
@@ -1275,9 +1296,15 @@ extern "C" int eesd_accept(eesd_ctx* c, const double* uniforms_or_null, int32_t*
     uu.u[K] = uniforms_or_null ? uniforms_or_null[K] : uniform53(g.seed, STREAM_RESAMPLE, c->round, 0, 0);
     for (int i = 0; i <= K; ++i)
         if (!(uu.u[i] >= 0.0 && uu.u[i] < 1.0)) return fail(c, EESD_EINVAL, "accept: uniform %d outside [0,1)", i);
-    HIP_TRY(c, smp_allow(accept_kernel, g.vocab));
-    hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, c->logits, c->p_rows, c->q_rows,
-                       c->blk_tok + 1, K, g.vocab, inv_temperature(c), greedy(c), 1, uu, c->result_dev, c->blk_tok, smp_use_lds(g.vocab));
+    if (lb16(c)) {
+        HIP_TRY(c, smp_allow(accept_kernel<bf16_t>, g.vocab));
+        hipLaunchKernelGGL(accept_kernel<bf16_t>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, (const bf16_t*)c->logits, c->p_rows, c->q_rows,
+                           c->blk_tok + 1, K, g.vocab, inv_temperature(c), greedy(c), 1, uu, c->result_dev, c->blk_tok, smp_use_lds(g.vocab));
+    } else {
+        HIP_TRY(c, smp_allow(accept_kernel<float>, g.vocab));
+        hipLaunchKernelGGL(accept_kernel<float>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, (const float*)c->logits, c->p_rows, c->q_rows,
+                           c->blk_tok + 1, K, g.vocab, inv_temperature(c), greedy(c), 1, uu, c->result_dev, c->blk_tok, smp_use_lds(g.vocab));
+    }
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipMemcpyAsync(c->h_result, c->result_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     if (K) HIP_TRY(c, hipMemcpyAsync(c->h_result + H_TOKS_AT, c->blk_tok + 1, K * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
@@ -1543,6 +1570,17 @@ extern "C" int eesd_debug_fill_cache(eesd_ctx* c, int32_t n_tokens, int32_t pend
     return EESD_OK;
 }
 
+// one row of bf16 logits, widened to fp32 on the host
+static int read_bf16_row(eesd_ctx* c, const void* dev_row, float* host_dst) {
+    std::vector<uint16_t> tmp(c->cfg.vocab);
+    HIP_TRY(c, hipMemcpy(tmp.data(), dev_row, tmp.size() * 2, hipMemcpyDeviceToHost));
+    for (size_t j = 0; j < tmp.size(); ++j) {
+        uint32_t u = (uint32_t)tmp[j] << 16;
+        memcpy(host_dst + j, &u, 4);
+    }
+    return EESD_OK;
+}
+
 extern "C" int eesd_debug_read(eesd_ctx* c, int what, int index, int32_t n_tokens, void* host_dst, size_t bytes) {
     if (!c) return EESD_EINVAL;
     if (!host_dst) return fail(c, EESD_EINVAL, "debug_read: null destination");
@@ -1553,12 +1591,14 @@ extern "C" int eesd_debug_read(eesd_ctx* c, int what, int index, int32_t n_token
         case EESD_READ_DRAFT_LOGITS:
         case EESD_READ_DRAFT_PROBS: {
             if (index < 0 || index >= g.k_cap || bytes < row) return fail(c, EESD_ERANGE, "debug_read: bad draft slot or size");
+            if (what == EESD_READ_DRAFT_LOGITS && lb16(c)) return read_bf16_row(c, logit_row(c, c->q_logits, index), (float*)host_dst);
             const float* src = (what == EESD_READ_DRAFT_LOGITS ? c->q_logits : c->q_rows) + (size_t)index * g.vocab;
             HIP_TRY(c, hipMemcpy(host_dst, src, row, hipMemcpyDeviceToHost));
             return EESD_OK;
         }
         case EESD_READ_VERIFY_LOGITS: {
             if (index < 0 || index >= MAX_ROWS || bytes < row) return fail(c, EESD_ERANGE, "debug_read: bad verify row or size");
+            if (lb16(c)) return read_bf16_row(c, logit_row(c, c->logits, index), (float*)host_dst);
             HIP_TRY(c, hipMemcpy(host_dst, c->logits + (size_t)index * g.vocab, row, hipMemcpyDeviceToHost));
             return EESD_OK;
         }
@@ -1675,9 +1715,45 @@ extern "C" int eesd_op_accept(const float* p_rows, const float* q_rows, const in
     hipStream_t st = (hipStream_t)hip_stream;
     int32_t* d_res = nullptr;
     if (hipMalloc((void**)&d_res, 2 * sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
-    hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(SMP_THREADS), 0, st, (const float*)nullptr, const_cast<float*>(p_rows), q_rows, drafts, K,
+    hipLaunchKernelGGL(accept_kernel<float>, dim3(1), dim3(SMP_THREADS), 0, st, (const float*)nullptr, const_cast<float*>(p_rows), q_rows, drafts, K,
                        vocab, 1.0f, greedy_flag, 0, uu, d_res, (int32_t*)nullptr, 0);
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = hipMemcpy(result, d_res, 2 * sizeof(int32_t), hipMemcpyDeviceToHost);
+    hipFree(d_res);
+    return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
+}
+
+extern "C" int eesd_op_accept_logits(const void* p_logits, int32_t logits_bf16, float* p_rows, const float* q_rows, const int32_t* drafts,
+                                     const double* uniforms, int32_t K, int32_t vocab, float temperature, void* hip_stream, int32_t* result) {
+    if (!p_logits || !result || K < 0 || K > ACC_MAX_K || vocab < 2 || !(temperature >= 0.f) || logits_bf16 < 0 || logits_bf16 > 1) return EESD_EINVAL;
+    if (K > 0 && !drafts) return EESD_EINVAL;
+    const int greedy_flag = temperature == 0.f;
+    if (!greedy_flag && (!uniforms || !p_rows || (K > 0 && !q_rows))) return EESD_EINVAL;
+    AcceptU uu;
+    memset(&uu, 0, sizeof uu);
+    if (!greedy_flag)
+        for (int i = 0; i <= K; ++i) {
+            if (!(uniforms[i] >= 0.0 && uniforms[i] < 1.0)) return EESD_EINVAL;
+            uu.u[i] = uniforms[i];
+        }
+    hipStream_t st = (hipStream_t)hip_stream;
+    int32_t* d_res = nullptr;
+    if (hipMalloc((void**)&d_res, 2 * sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
+    const float inv_t = greedy_flag ? 1.0f : 1.0f / temperature;
+    hipError_t e;
+    if (logits_bf16) {
+        e = smp_allow(accept_kernel<bf16_t>, vocab);
+        if (e == hipSuccess)
+            hipLaunchKernelGGL(accept_kernel<bf16_t>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(vocab), st, (const bf16_t*)p_logits, p_rows, q_rows, drafts, K, vocab,
+                               inv_t, greedy_flag, 1, uu, d_res, (int32_t*)nullptr, smp_use_lds(vocab));
+    } else {
+        e = smp_allow(accept_kernel<float>, vocab);
+        if (e == hipSuccess)
+            hipLaunchKernelGGL(accept_kernel<float>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(vocab), st, (const float*)p_logits, p_rows, q_rows, drafts, K, vocab,
+                               inv_t, greedy_flag, 1, uu, d_res, (int32_t*)nullptr, smp_use_lds(vocab));
+    }
+    if (e == hipSuccess) e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e == hipSuccess) e = hipMemcpy(result, d_res, 2 * sizeof(int32_t), hipMemcpyDeviceToHost);
     hipFree(d_res);
@@ -1691,9 +1767,9 @@ extern "C" int eesd_op_softmax_sample(const float* logits, float* probs, int32_t
     hipStream_t st = (hipStream_t)hip_stream;
     int32_t* d_tok = nullptr;
     if (hipMalloc((void**)&d_tok, sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
-    hipError_t e = smp_allow(softmax_sample_kernel, vocab);
+    hipError_t e = smp_allow(softmax_sample_kernel<float>, vocab);
     if (e == hipSuccess) {
-        hipLaunchKernelGGL(softmax_sample_kernel, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(vocab), st, logits, probs, vocab,
+        hipLaunchKernelGGL(softmax_sample_kernel<float>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(vocab), st, logits, probs, vocab,
                            temperature > 0.f ? 1.0f / temperature : 1.0f, temperature == 0.f, u, -1, d_tok, smp_use_lds(vocab));
         e = hipGetLastError();
     }

@@ -32,8 +32,8 @@ def test_library_exports_every_declared_function():
 
 def test_struct_sizes_match_the_header_layout():
     import paper_2406_03853_amd.binding as b
-    # 13 int32/float fields (52) + pad to 8 + seed + 2 doubles + 6 int32 = 112
-    assert ctypes.sizeof(b._Config) == 112
+    # 15 int32/float fields (60) + pad to 8 + seed + 2 doubles + 7 int32 + pad to 8 = 120
+    assert ctypes.sizeof(b._Config) == 120
     assert ctypes.sizeof(b._Layer) == 48
     assert ctypes.sizeof(b._Weights) == 4 * 8 + 48 + 2 * 8
     assert ctypes.sizeof(b._Stats) == 4 * 8 + 9 * 8

@@ -222,3 +222,88 @@ def test_accept_special_rows():
     d = torch.tensor([tops[0], tops[1], (tops[2] + 1) % V], dtype=torch.int32, device="cuda")
     assert pk.op_accept(torch.from_numpy(lg).cuda(), None, d, None, greedy=True) == (2, int(tops[2]))
     assert pk.op_accept(torch.from_numpy(lg).cuda(), None, d, None, greedy=True) == orc.decide_accept(lg, None, d.cpu().numpy(), None, None, True)
+
+
+@pytest.mark.parametrize("K", [0, 1, 3, 7, 15])
+@pytest.mark.parametrize("bf16", [1, 0])
+def test_accept_on_logit_rows_bit_exact(K, bf16):
+    """The verification tail on 32000-way logit rows stored as bf16 (and as fp32): the bf16 values are the INPUT of
+    both sides.  The probability rows the kernel leaves equal the fp64 softmax of those logits to fp32 rounding, and
+    the decision is exactly the oracle's rule on the kernel's own rows with the same uniforms.  Greedy: argmax over
+    exactly representable values, so the oracle's rule on the widened logits must agree with no row read back."""
+    require_gpu()
+    pk = _pk()
+    V = 32000
+    rej = 0
+    for s in range(6):
+        lg32 = si.make_logit_rows(K + 1, V, seed=1000 * K + s)
+        lg = torch.from_numpy(lg32).cuda()
+        if bf16:
+            lg = lg.to(torch.bfloat16)
+        lg_in = lg.float().cpu().numpy()                 # what both sides are given
+        T = [1.0, 0.8][s % 2]
+        p_ref = orc.softmax(lg_in.astype(np.float64) / T)
+        # q close to p so that accept / reject both occur along the block
+        q = (p_ref[:K] * np.exp(0.6 * np.random.default_rng(s).standard_normal((K, V)))) if K else np.zeros((0, V))
+        if K:
+            q = (q / q.sum(axis=1, keepdims=True)).astype(np.float32)
+        drafts = np.array([orc.decide_sample(q[i], u) for i, u in enumerate(si.make_uniforms(K, seed=7 * s))], np.int32)
+        us = si.make_uniforms(K + 1, seed=31 * s + K)
+        p_rows = torch.full((K + 1, V), float("nan"), device="cuda")
+        qd = torch.from_numpy(np.ascontiguousarray(q, np.float32)).cuda() if K else None
+        dd = torch.from_numpy(drafts).cuda()
+        a, y = pk.op_accept_logits(lg, p_rows, qd, dd, us, T)
+        p_gpu = p_rows.cpu().numpy()
+        assert np.isfinite(p_gpu[: a + 1]).all()
+        assert np.max(np.abs(p_gpu[: a + 1] - p_ref[: a + 1])) < 2e-6 * np.max(p_ref)
+        assert orc.decide_accept(p_gpu, q.astype(np.float32) if K else None, drafts, us[:K], us[K], greedy=False) == (a, y), (s, a, y)
+        rej += a < K
+        # greedy on the same logits
+        tops = lg_in.argmax(axis=1)
+        dg = tops[:K].astype(np.int32).copy()
+        if K >= 2:
+            dg[K // 2] = (dg[K // 2] + 1) % V              # first mismatch in the middle of the block
+        got = pk.op_accept_logits(lg, None, None, torch.from_numpy(dg).cuda(), None, 0.0)
+        assert got == orc.decide_accept(lg_in, None, dg, None, None, True)
+        assert got[0] == (K // 2 if K >= 2 else K)
+    if K >= 3:
+        assert rej > 0
+
+
+def test_round_with_bf16_logits_matches_oracle():
+    """A context whose LM heads store bf16 logits (the 70B verify micro-benchmark's setting): logits within the bf16
+    tolerance of the oracle's, and the round's decisions exactly the rule on the GPU's own probability rows."""
+    require_gpu()
+    pk = _pk()
+    from gpu_common import make_pair, rel_err
+    shape = si.TINY_GQA_BF16
+    V = shape["vocab"]
+    o, g = make_pair(shape, 13, 96, 1.0, k_cap=5, seed=3, logits_bf16=1, weight_layout=1)
+    prompt = si.make_prompt(19, V, 2)
+    o.prefill(prompt)
+    t = g.prefill(prompt)
+    assert orc.decide_sample(g.verify_probs(0), orc.uniform(3, orc.STREAM_RESAMPLE, 0)) == t
+    o.pending = t
+    for K in (4, 2, 5, 0):
+        ds = []
+        for i in range(K):
+            d = g.draft_step()
+            assert orc.decide_sample(g.draft_probs(i), orc.uniform(3, orc.STREAM_DRAFT, o.rnd, i)) == d
+            o.draft_step(force_token=d)
+            got = g.draft_logits(i)
+            assert np.array_equal(got, torch.from_numpy(got).to(torch.bfloat16).float().numpy())     # bf16 values
+            assert rel_err(got, o.q_logits[i]) < TOL_BF16
+            ds.append(d)
+        pl = o.verify()
+        g.verify()
+        a, y = g.accept()
+        p = np.full((K + 1, V), np.nan, np.float32)
+        for i in range(a + 1):
+            p[i] = g.verify_probs(i)
+        q = np.stack([g.draft_probs(i) for i in range(K)]) if K else None
+        us = [orc.uniform(3, orc.STREAM_ACCEPT, o.rnd, i) for i in range(K)]
+        assert orc.decide_accept(p, q, ds, us, orc.uniform(3, orc.STREAM_RESAMPLE, o.rnd), False) == (a, y)
+        for i in range(K + 1):
+            assert rel_err(g.verify_logits(i), pl[i]) < TOL_BF16
+        o.rollback(a, y)
+        g.rollback(a)
