@@ -45,22 +45,15 @@ def oracle_sample_weights(w_gpu, shape, si):
     return si.weights_to_numpy(sub)
 
 
-def cpu_baseline(w, shape, temperature, mean_k, mean_commit, si):
-    """The oracle as it stands, timed on this box's host cores on a bounded sample: the same
-    weights at depth L=2, N=1, a few rounds; per-parameter time scaled to the full depth."""
-    import numpy as np
+def _oracle_rounds(w, temperature, si, budget_s, max_rounds):
+    """A few rounds (1 draft step + 1 two-row verify) of the oracle on the depth-reduced weights: mean seconds per pass."""
     from oracle import eesd_oracle as orc
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
     sh = w["shape"]
     o = orc.OracleEESD(w, max_seq=64, temperature=temperature, seed=0, k_cap=4)
     o.prefill(si.make_prompt(4, sh["vocab"], 0))
     t_d, t_v, rounds = 0.0, 0.0, 0
     t_start = time.perf_counter()
-    while rounds < 2 or (time.perf_counter() - t_start < 12.0 and rounds < 6):
+    while rounds < 2 or (time.perf_counter() - t_start < budget_s and rounds < max_rounds):
         t0 = time.perf_counter()
         o.draft_step()
         t1 = time.perf_counter()
@@ -71,32 +64,63 @@ def cpu_baseline(w, shape, temperature, mean_k, mean_commit, si):
         t_d += t1 - t0
         t_v += t2 - t1
         rounds += 1
+    return t_d / rounds, t_v / rounds, rounds
+
+
+def cpu_baseline(w, shape, temperature, mean_k, mean_commit, si):
+    """The oracle as it stands, timed on this box's host cores on a bounded sample: the same
+    weights at depth L=2, N=1, a few rounds; per-parameter time scaled to the full depth.  Two legs: the
+    threads numpy's BLAS takes by itself, and one thread."""
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threadpool_limits = None
+        cores = os.cpu_count() or 1
+    try:
+        import psutil
+        ram_gb = psutil.virtual_memory().total / 2 ** 30
+    except Exception:
+        ram_gb = None
+    sh = w["shape"]
     p_layer, p_head = si.layer_param_count(sh), sh["vocab"] * sh["d_model"]
     p_kv = 2 * sh["n_kv_heads"] * sh["head_dim"] * sh["d_model"]
-    c1 = (t_d / rounds) / (2 * p_layer + p_head)              # seconds per parameter, one row
-    c2 = (t_v / rounds) / (2 * p_layer + p_kv + p_head)       # seconds per parameter, two rows
     L, N = shape["n_layers"], shape["n_draft_layers"]
-    t_draft_full = c1 * ((N + 1) * p_layer + p_head)
-    t_verify_full = c2 * (L * p_layer + p_kv + p_head)
-    tok_s = mean_commit / (mean_k * t_draft_full + t_verify_full)
-    return dict(value=tok_s, unit="tokens/s", cores=int(cores), kind="oracle",
-                sample=f"{rounds} rounds (1 draft step + 1 two-row verify) of the fp64 numpy oracle on the first 2 layers "
-                       f"+ early-exit layer + heads of the same weights; seconds per parameter scaled to L={L}, N={N} "
-                       f"with the GPU run's mean K={mean_k:.2f} and {mean_commit:.2f} tokens per round",
-                draft_step_s=t_draft_full, verify_s=t_verify_full)
+
+    def scale(td, tv):
+        c1 = td / (2 * p_layer + p_head)              # seconds per parameter, one row
+        c2 = tv / (2 * p_layer + p_kv + p_head)       # seconds per parameter, two rows
+        t_draft_full = c1 * ((N + 1) * p_layer + p_head)
+        t_verify_full = c2 * (L * p_layer + p_kv + p_head)
+        return mean_commit / (mean_k * t_draft_full + t_verify_full), t_draft_full, t_verify_full
+
+    td, tv, rounds = _oracle_rounds(w, temperature, si, 10.0, 6)
+    tok_s, t_draft_full, t_verify_full = scale(td, tv)
+    out = dict(value=tok_s, unit="tokens/s", cores=int(cores), kind="oracle",
+               sample=f"{rounds} rounds (1 draft step + 1 two-row verify) of the fp64 numpy oracle on the first 2 layers "
+                      f"+ early-exit layer + heads of the same weights; seconds per parameter scaled to L={L}, N={N} "
+                      f"with the GPU run's mean K={mean_k:.2f} and {mean_commit:.2f} tokens per round (depth-reduced because an fp64 "
+                      f"pass over all {L} layers takes minutes per token on the host; host RAM {ram_gb:.0f} GiB)" if ram_gb else "",
+               draft_step_s=t_draft_full, verify_s=t_verify_full, host_ram_GiB=ram_gb)
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            td1, tv1, r1 = _oracle_rounds(w, temperature, si, 8.0, 2)
+        tok1, d1, v1 = scale(td1, tv1)
+        out["single_thread"] = dict(value=tok1, unit="tokens/s", cores=1, draft_step_s=d1, verify_s=v1, sample=f"{r1} rounds, same scaling")
+    return out
 
 
-def latency_sweep(ctx, torch, cache_tokens, k_cap, b_draft, shape, si):
-    """Draft-step and verify-pass latency for fixed K over a cache of `cache_tokens` positions
+def latency_sweep(ctx, torch, cache_tokens, ks, shape, si):
+    """Draft-step, verify-pass and accept latency for fixed K over a cache of `cache_tokens` positions
     (filled with a deterministic pattern: attention cost depends on the shape only)."""
     res = {}
     L = shape["n_layers"]
-    for K in [k for k in (0, 1, 2, 3, 5, 7, 10, 15) if k <= k_cap]:
-        ctx.fill_cache(cache_tokens, 1)
-        td = tv = 0.0
+    for K in ks:
+        td = tv = ta = 0.0
         reps = 5
         for r in range(reps + 1):
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            ctx.fill_cache(cache_tokens, 1)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
             ev[0].record()
             for _ in range(K):
                 ctx.draft_step(sync=False)
@@ -104,14 +128,74 @@ def latency_sweep(ctx, torch, cache_tokens, k_cap, b_draft, shape, si):
             ctx.verify()
             ev[2].record()
             ctx.accept()
+            ev[3].record()
+            torch.cuda.synchronize()
             ctx.rollback_forced(0, 1)
             if r:
                 td += ev[0].elapsed_time(ev[1])
                 tv += ev[1].elapsed_time(ev[2])
+                ta += ev[2].elapsed_time(ev[3])
         b_verify = pass_bytes(shape, L, True, cache_tokens, si)
-        res[str(K)] = {"verify_rows": K + 1, "verify_ms": tv / reps, "verify_GBps": b_verify / (tv / reps * 1e-3) / 1e9,
-                       "draft_step_ms": (td / reps / K) if K else None}
+        res[str(K + 1)] = {"verify_rows": K + 1, "verify_ms": tv / reps, "verify_GBps": b_verify / (tv / reps * 1e-3) / 1e9,
+                           "verify_frac_of_peak": b_verify / (tv / reps * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           "accept_us": ta / reps * 1e3, "draft_step_ms": (td / reps / K) if K else None}
     return res
+
+
+def summarise(stats, shape, n_prompt, max_new, bf16, si):
+    """Per-pass figures of a list of eesd_generate statistics."""
+    st = stats[-1]
+    rounds = sum(s.rounds for s in stats)
+    drafted = sum(s.drafted for s in stats)
+    accepted = sum(s.accepted for s in stats)
+    mean_k = drafted / max(1, rounds)
+    mean_commit = (accepted + rounds) / max(1, rounds)
+    v_d = accepted / max(1, drafted)       # Section 4.1 "Metrics", over all steps
+    r_d = accepted / max(1, sum(s.generated for s in stats))
+    ms_draft = sum(s.ms_draft for s in stats) / max(1, drafted)
+    ms_verify = sum(s.ms_verify for s in stats) / max(1, rounds)
+    ms_accept = sum(s.ms_accept for s in stats) / max(1, rounds)
+    ms_other = sum(s.ms_other for s in stats) / max(1, rounds)       # host turn-around between rounds
+    N, L = shape["n_draft_layers"], shape["n_layers"]
+    ctx_mid = n_prompt + max_new // 2      # bytes are taken at the middle of the generation
+    b_draft = pass_bytes(shape, N + 1, True, ctx_mid, si)
+    b_verify = pass_bytes(shape, L, True, ctx_mid, si) + 2 * shape["n_kv_heads"] * shape["head_dim"] * shape["d_model"] * (2 if bf16 else 4)
+    out = {"draft_step_ms": ms_draft, "verify_ms": ms_verify, "accept_ms": ms_accept, "host_gap_ms_per_round": ms_other,
+           "draft_step_GBps": b_draft / (ms_draft * 1e-3) / 1e9 if ms_draft else None,
+           "verify_GBps": b_verify / (ms_verify * 1e-3) / 1e9 if ms_verify else None,
+           "draft_step_bytes": b_draft, "verify_bytes": b_verify, "bytes_note": "weights of the layers a pass runs + its LM head + cached keys/values at mid-generation context",
+           "mean_K": mean_k, "tokens_per_round": mean_commit, "v_d": v_d, "r_d": r_d,
+           "hm": 200.0 * v_d * r_d / (v_d + r_d) if v_d + r_d else 0.0,
+           "ts_alpha": st.alpha, "ts_beta": st.beta}
+    # context only: the speed model of the paper's Appendix D, speedup = v_d / ((alpha - v_d) r_d + v_d) with
+    # alpha = T_draft / T_target, at the acceptance the paper reports for its TRAINED early-exit layers
+    # (Gsm8k, Beta-TS) and at this run's measured pass times (T_target taken as one verify pass)
+    if ms_draft and ms_verify:
+        alpha = ms_draft / ms_verify
+        vd_p, rd_p = (0.52, 0.68) if shape["d_model"] >= 8192 else (0.50, 0.67)
+        out["alpha_Td_over_Tt"] = alpha
+        out["speed_model_at_paper_acceptance"] = {"v_d": vd_p, "r_d": rd_p, "speedup_vs_autoregressive": vd_p / ((alpha - vd_p) * rd_p + vd_p)}
+    return out, mean_k, mean_commit
+
+
+def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperature, tiled, steps):
+    """A short untimed-by-the-headline generation run on given weights: tokens/s and per-pass figures."""
+    max_seq = (n_prompt + max_new + k_cap + 2 + 63) // 64 * 64
+    ctx = pk.EESD(w, max_seq=max_seq, temperature=temperature, seed=0, k_cap=k_cap, kv_page=64,
+                  weight_layout=pk.WEIGHTS_TILED if tiled else pk.WEIGHTS_ROW_MAJOR)
+    prompts = [si.make_prompt(n_prompt, shape["vocab"], 100 + i) for i in range(steps)]
+    ctx.generate(prompts[-1], max_new)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stats = [ctx.generate(prompts[i], max_new)[1] for i in range(steps)]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    passes, _, _ = summarise(stats, shape, n_prompt, max_new, shape["dtype"] == "bf16", si)
+    passes["tokens_per_s"] = steps * max_new / dt
+    passes["steps"] = steps
+    passes["temperature"] = temperature
+    ctx.close()
+    return passes
 
 
 def stored_traffic(workload):
@@ -144,8 +228,10 @@ def main():
                     help="gamma of synth_inputs.make_weights(correlated_draft=gamma): a synthetic draft model that agrees with the "
                          "target often (independent random weights almost never do under greedy decoding)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip what the default run reports beside the timed steps: the greedy run, latency versus verify rows, the 13B-shape passes")
     ap.add_argument("--latency-sweep", action="store_true",
-                    help="also report draft-step and verify-pass latency versus K over a pre-filled cache (outside the timed region)")
+                    help="(non-default workloads) also report draft-step and verify-pass latency versus K over a pre-filled cache")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's 1 GiB copy kernel a few times (reference for hardware-counter runs)")
     args = ap.parse_args()
@@ -167,23 +253,26 @@ def main():
     if args.tree_width >= 2:
         args.temperature = 0.0
         k_cap = min(k_cap, 15 // args.tree_width)
+    extras = args.workload == "70b" and not args.headline_only and args.tree_width < 2 and args.controller == "beta" \
+        and args.draft_correlation is None and not args.row_major_weights
     t0 = time.perf_counter()
     w = si.make_weights(shape, seed=wseed, device="cuda", correlated_draft=args.draft_correlation)
     torch.cuda.synchronize()
     t_weights = time.perf_counter() - t0
     cpu_w = None if args.no_cpu_baseline else oracle_sample_weights(w, shape, si)
-    tiled = shape["dtype"] == "bf16" and not args.row_major_weights
+    bf16 = shape["dtype"] == "bf16"
+    tiled = bf16 and not args.row_major_weights
     if tiled:      # one-off rearrangement by the library's own kernel, matrix by matrix
         w = pk.pack_weights(w)
         torch.cuda.synchronize()
+    layout = pk.WEIGHTS_TILED if tiled else pk.WEIGHTS_ROW_MAJOR
     max_seq = n_prompt + max_new + k_cap * max(1, args.tree_width) + 2
     sweep_tokens = 2048 if args.workload == "70b" else n_prompt       # cache length of the latency sweep
     if args.latency_sweep:
         max_seq = max(max_seq, sweep_tokens + k_cap + 2)
     max_seq = (max_seq + 63) // 64 * 64
     ctx = pk.EESD(w, max_seq=max_seq, temperature=args.temperature, seed=0, k_cap=k_cap, kv_page=64, tree_width=args.tree_width, verify_reuse=int(args.verify_reuse),
-                  weight_layout=pk.WEIGHTS_TILED if tiled else pk.WEIGHTS_ROW_MAJOR,
-                  ts_mode=pk.TS_CALI if args.controller == "cali" else pk.TS_BETA)
+                  weight_layout=layout, ts_mode=pk.TS_CALI if args.controller == "cali" else pk.TS_BETA)
     if args.controller == "cali":
         cw = si.make_cali_weights(shape, wseed, device="cuda")
         ctx.set_calibration(pk.pack_calibration(cw) if tiled else cw, 0.2, 0.5, 0.5)
@@ -201,9 +290,7 @@ def main():
     for _ in range(args.warmup):
         ctx.generate(prompts[-1], max_new)
     torch.cuda.synchronize()
-    bf16 = shape["dtype"] == "bf16"
-    # dominant kernel: the gate/up product of the verify pass (MFMA family on bf16, VALU on fp32)
-    ctx.profile_begin(1 if bf16 else 0, 2, shape["d_model"])
+    # ---- the timed region: exactly `steps` whole generations, nothing else on the stream ----
     t0 = time.perf_counter()
     stats = []
     for i in range(args.steps):
@@ -211,22 +298,15 @@ def main():
         stats.append(st)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # ---- after it: one more generation with a HIP event pair around every launch of the dominant kernel
+    # (the gate/up product of the draft and verify passes: MFMA family on bf16, VALU on fp32) ----
+    ctx.profile_begin(1 if bf16 else 0, 2, shape["d_model"])
+    ctx.generate(prompts[0], max_new)
     n_launch, ms_kernel = ctx.profile_end()
 
-    st = stats[-1]
-    rounds = sum(s.rounds for s in stats)
-    mean_k = sum(s.drafted for s in stats) / max(1, rounds)
-    mean_commit = sum(s.accepted + s.rounds for s in stats) / max(1, rounds)
-    v_d = sum(s.accepted for s in stats) / max(1, sum(s.drafted for s in stats))       # Section 4.1 "Metrics", over all steps
-    r_d = sum(s.accepted for s in stats) / max(1, sum(s.generated for s in stats))
-    ms_draft = sum(s.ms_draft for s in stats) / max(1, sum(s.drafted for s in stats))
-    ms_verify = sum(s.ms_verify for s in stats) / max(1, rounds)
-    ms_accept = sum(s.ms_accept for s in stats) / max(1, rounds)
-    ms_other = sum(s.ms_other for s in stats) / max(1, rounds)       # host turn-around between rounds
+    passes, mean_k, mean_commit = summarise(stats, shape, n_prompt, max_new, bf16, si)
+    passes["weight_init_s"] = t_weights
     N, L = shape["n_draft_layers"], shape["n_layers"]
-    ctx_mid = n_prompt + max_new // 2
-    b_draft = pass_bytes(shape, N + 1, True, ctx_mid, si)
-    b_verify = pass_bytes(shape, L, True, ctx_mid, si) + 2 * shape["n_kv_heads"] * shape["head_dim"] * shape["d_model"] * (2 if bf16 else 4)
     esz = 2 if bf16 else 4
     kernel_bytes = 2 * shape["d_ff"] * shape["d_model"] * esz          # weights of one gate/up product
     avg_kernel_s = (ms_kernel / max(1, n_launch)) * 1e-3
@@ -253,27 +333,40 @@ def main():
                      else "gemm_valu_kernel<SWIGLU>",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": stored_traffic(args.workload), "launches_timed": n_launch, "avg_kernel_us": avg_kernel_s * 1e6,
-                     "bytes_per_launch": kernel_bytes},
-        "passes": {"draft_step_ms": ms_draft, "verify_ms": ms_verify, "accept_ms": ms_accept, "host_gap_ms_per_round": ms_other,
-                   "draft_step_GBps": b_draft / (ms_draft * 1e-3) / 1e9 if ms_draft else None,
-                   "verify_GBps": b_verify / (ms_verify * 1e-3) / 1e9 if ms_verify else None,
-                   "draft_step_bytes": b_draft, "verify_bytes": b_verify,
-                   "mean_K": mean_k, "tokens_per_round": mean_commit, "v_d": v_d, "r_d": r_d,
-                   "hm": 200.0 * v_d * r_d / (v_d + r_d) if v_d + r_d else 0.0,
-                   "ts_alpha": st.alpha, "ts_beta": st.beta, "weight_init_s": t_weights},
+                     "bytes_per_launch": kernel_bytes,
+                     "timed_in": "one extra generation after the timed steps (an event pair around every launch)",
+                     "pass_frac": {"draft": (passes["draft_step_GBps"] or 0.0) / HBM_PEAK_GBS, "verify": (passes["verify_GBps"] or 0.0) / HBM_PEAK_GBS}},
+        "passes": passes,
     }
-    # context only: the speed model of the paper's Appendix D, speedup = v_d / ((alpha - v_d) r_d + v_d) with
-    # alpha = T_draft / T_target, at the acceptance the paper reports for its TRAINED early-exit layers
-    # (Gsm8k, Beta-TS) and at this run's measured pass times (T_target taken as one verify pass)
-    if ms_draft and ms_verify:
-        alpha = ms_draft / ms_verify
-        vd_p, rd_p = (0.52, 0.68) if shape["d_model"] >= 8192 else (0.50, 0.67)
-        out["passes"]["alpha_Td_over_Tt"] = alpha
-        out["passes"]["speed_model_at_paper_acceptance"] = {"v_d": vd_p, "r_d": rd_p, "speedup_vs_autoregressive": vd_p / ((alpha - vd_p) * rd_p + vd_p)}
-    if args.latency_sweep:
-        out["latency_vs_K"] = latency_sweep(ctx, torch, sweep_tokens, k_cap, b_draft, shape, si)
+    if args.latency_sweep and not extras:
+        ks = [k for k in (0, 1, 2, 3, 5, 7, 10, 15) if k <= k_cap]
+        out["latency_vs_K"] = latency_sweep(ctx, torch, sweep_tokens, ks, shape, si)
+    ctx.close()
+    del ctx
+    if extras:
+        # greedy decoding on the same weights (random weights: a greedy draft almost never matches, K collapses to 1)
+        out["passes_T0"] = side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, 0.0, tiled, 2)
+        # the verify micro-benchmark of the 70B shape: one block of 1, 2, 4, 8, 16 rows over a 2048-token cache, then the
+        # accept / resample kernel on 32000-way bf16 logits with the context's seeded uniforms
+        c4 = pk.EESD(w, max_seq=2048 + 64, temperature=1.0, seed=0, k_cap=15, kv_page=64, weight_layout=layout, logits_bf16=1)
+        out["latency_vs_K"] = {"cache_tokens": 2048, "logits": "bf16", "by_verify_rows": latency_sweep(c4, torch, 2048, (0, 1, 3, 7, 15), shape, si)}
+        c4.close()
+        del c4
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cpu_w, shape, args.temperature, mean_k, mean_commit, si)
+    if extras:
+        # the 13B shape: the 70B weights go first
+        del w
+        torch.cuda.empty_cache()
+        key13, seed13, np13, new13, cap13 = WORKLOADS["13b"]
+        shape13 = getattr(si, key13)
+        w13 = pk.pack_weights(si.make_weights(shape13, seed=seed13, device="cuda"))
+        torch.cuda.synchronize()
+        p13 = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 1.0, True, 4)
+        p13["workload"] = f"full EESD generation, {shape13['name']} (L={shape13['n_layers']}, N={shape13['n_draft_layers']}), prompt {np13}, {new13} new tokens, K cap {cap13}, temperature 1"
+        p13["pass_frac"] = {"draft": p13["draft_step_GBps"] / HBM_PEAK_GBS, "verify": p13["verify_GBps"] / HBM_PEAK_GBS}
+        out["passes_13b"] = p13
+        out["passes_13b_T0"] = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 0.0, True, 2)
     print(json.dumps(out))
 
 
