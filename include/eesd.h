@@ -136,7 +136,9 @@ typedef struct eesd_stats {
  * and starts a new sequence.
  */
 
-/* Allocates the paged KV cache (L target layers, the first N shared with the draft
+/* Algorithm 1, REQUIRE line: the target model, the draft model (the same weights' first N layers, the early-exit
+ * layer and its head: Section 3.1), the hyper-parameters of the controller and the decoding limits, as one context.
+ * Allocates the paged KV cache (L target layers, the first N shared with the draft
  * model, plus the early-exit layer's own cache) and all scratch memory on the current
  * device.  hip_stream is a hipStream_t (NULL = the default stream).  Weights are
  * borrowed.  Errors: EESD_EINVAL (null pointer, unsupported shape), EESD_ENOMEM. */
@@ -165,8 +167,11 @@ int eesd_verify(eesd_ctx* ctx);
  * written to cache slot base + row, rotated for position base + depth, and attends to the cache,
  * row 0, the j = 0 rows of the depths above it, and itself. */
 
-/* Accept / resample.  Greedy: drafts are kept while equal to the target's top-1; the
- * next token is the top-1 after them.  Sampling: draft i is accepted iff
+/* Algorithm 1, steps 15-17, on the logits eesd_verify left: which drafts the target keeps, and the token it
+ * contributes after them.  Greedy (Section 4.1, footnote: one top-1 candidate per step, kept while consistent with
+ * the target's top-1 token): drafts are kept while equal to the target's top-1; the
+ * next token is the top-1 after them.  Sampling (the speculative-sampling rule of the works the paper builds on,
+ * which keeps the output distributed as auto-regressive decoding, Section 1): draft i is accepted iff
  * u_i * q_i(d_i) < p_i(d_i); the first rejected position is resampled from
  * norm(max(0, p - q)); if all K pass, a bonus token is drawn from p_{K+1}.
  * uniforms_or_null: HOST array of K+1 doubles in [0,1) (K accept tests, then the
@@ -254,7 +259,10 @@ int eesd_host_cali_decide(double sigma_m, double sigma_s, double theta_hat, int6
                           int64_t round, int32_t slot, double* theta, int32_t* chi);
 int eesd_host_cali_update(double* theta_hat, double* weight, int64_t* n, int32_t n_accepted, int32_t n_drafted, int32_t reading);
 
-/* ---- test and benchmark hooks ------------------------------------------------------- */
+/* =====================================================================================================
+ * TEST AND BENCHMARK HOOKS - not part of decoding.  Everything from here to the stand-alone kernels reads internal
+ * state, forces tokens, times launches or turns launch-shape knobs; no product code path needs any of it.
+ * ===================================================================================================== */
 enum {
     EESD_READ_DRAFT_LOGITS = 0,  /* index = draft slot i (0-based): vocab floats */
     EESD_READ_DRAFT_PROBS = 1,   /* index = draft slot: vocab floats (sampling mode only) */
@@ -300,7 +308,9 @@ int eesd_debug_profile_end(eesd_ctx* ctx, int32_t* n_launches, double* total_ms)
  * for this kernel, whose traffic is known (bytes read + bytes written).  Does not synchronise. */
 int eesd_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
-/* Launch-shape knobs for benchmark sweeps (process-wide; 0 restores the built-in heuristic):
+/* Launch-shape knobs for benchmark sweeps.  PROCESS-WIDE: they change the launch heuristics of every context of the
+ * process, are not synchronised with running calls and are meant for single-threaded sweeps only (0, or -1 for
+ * "fuse_norm", restores the built-in heuristic):
  * "valu_nw", "valu_tpw", "valu_rp", "mfma_nw", "mfma_ksplit", "fuse_norm", "mfma_tile", "tile_kc", "tile_nwt", "pf_kc",
  * "attn_split", "mfma_min_m", "nw_plain", "nw_resid", "nw_swiglu", "nw_qkv" (waves per workgroup of the per-tile
  * product by epilogue). */
@@ -326,7 +336,8 @@ int eesd_op_softmax_sample(const float* logits, float* probs, int32_t vocab, flo
 /* Y[m][r] = sum_k X[m][k] W[r][k]: the weight-streaming product of the draft (M = 1), verify
  * (M = K+1 <= 16) and prefill (M <= 128, bf16 MFMA family, out % 64 == 0, in % 256 == 0) passes
  * without prologue or epilogue.  W: DEVICE [out][in] in dtype (weight_layout EESD_WEIGHTS_TILED:
- * packed with kind EESD_PACK_PLAIN); X: DEVICE fp32 [M][in]; Y: DEVICE fp32 [M][out]; path: EESD_GEMM_*. */
+ * packed with kind EESD_PACK_PLAIN); X: DEVICE fp32 [M][in]; Y: DEVICE fp32 [M][out]; path: EESD_GEMM_*.
+ * The bf16 path stages the activation rows in one buffer per process: calls that overlap on the GPU race. */
 int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,
                  int32_t dtype, int32_t path, int32_t weight_layout, void* hip_stream);
 

@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -200,7 +201,9 @@ static int device_cu_count() {
 // Dynamic LDS above the default limit has to be granted per kernel; remember what was granted.
 static hipError_t allow_lds(const void* fn, size_t bytes) {
     static std::vector<std::pair<const void*, size_t>> done;
+    static std::mutex mu;          // contexts of different threads share the list
     if (bytes <= 48 * 1024) return hipSuccess;
+    std::lock_guard<std::mutex> lock(mu);
     for (auto& p : done)
         if (p.first == fn) {
             if (p.second >= bytes) return hipSuccess;
@@ -998,7 +1001,10 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if (c->n_cu < 1) return bail(EESD_EDEVICE);
     {
         const bool grouped = g.weight_layout == EESD_WEIGHTS_TILED && pack_n_groups(d, c->n_cu) != d / 16;
-        c->ssq_slots = grouped ? c->n_cu * GRP_MAX_TILES : d / 16;     // every row group reports GRP_MAX_TILES partial sums of squares per row
+        // a residual product leaves one partial sum of squares per row and tile: d / 16, or, dealt to one row group per CU,
+        // (tiles of the largest group) per group
+        const int tmax = ((((d / 4) + c->n_cu - 1) / c->n_cu) * 4 + 15) / 16;
+        c->ssq_slots = grouped ? c->n_cu * tmax : d / 16;
     }
     {
         const int qkv_rows = (g.n_heads + 2 * g.n_kv_heads) * g.head_dim, kv_rows = 2 * g.n_kv_heads * g.head_dim;
@@ -1815,6 +1821,8 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
         // bf16 staging rows of the activations: one buffer per process, grown on demand, kept
         static bf16_t* xb = nullptr;
         static size_t xb_elems = 0;
+        static std::mutex mu;      // guards the growth; calls that overlap on the GPU still share the rows (see the header)
+        std::lock_guard<std::mutex> lock(mu);
         const size_t need = (size_t)PREFILL_ROWS * in;
         if (need > xb_elems) {
             if (hipDeviceSynchronize() != hipSuccess) return EESD_EDEVICE;
