@@ -328,7 +328,7 @@ def main():
                                + (", verify reuses the draft steps' layer-N hidden states" if args.verify_reuse else "")
                                + (", calibrated controller with a random predictor" if args.controller == "cali" else "")
                                + (f", draft correlated with the target (gamma {args.draft_correlation:g})" if args.draft_correlation is not None else ""),
-                   "prefill": "included in every step (128-row blocks, tiled MFMA product)" if bf16 else "included in every step (16-row blocks)"},
+                   "prefill": "included in every step (blocks of up to 512 rows, MFMA GEMM on tile-major weights)" if bf16 else "included in every step (16-row blocks)"},
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<SWIGLU> (gate/up product of the draft and verify passes)" if bf16
                      else "gemm_valu_kernel<SWIGLU>",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

@@ -276,9 +276,10 @@ enum {
     EESD_READ_CALI_STATE = 9,    /* three doubles: theta_hat, the observations behind it, verifications n */
     EESD_READ_VERIFY_PROBS = 10, /* index = verify row i: vocab floats, the probability row the last eesd_accept judged draft i on
                                     (sampling mode; rows 0..a only: the accept kernel stops at the first rejection) */
-    EESD_READ_LAUNCH_COUNTS = 11 /* 16 int32: weight-streaming product launches since eesd_create, [kernel][epilogue] with kernel
+    EESD_READ_LAUNCH_COUNTS = 11 /* 20 int32: weight-streaming product launches since eesd_create, [kernel][epilogue] with kernel
                                     0 = VALU family, 1 = one workgroup per 16-row tile, 2 = one workgroup per row group,
-                                    3 = tiles sharing the activations through LDS; epilogue 0 LM head, 1 residual, 2 SwiGLU, 3 QKV */
+                                    3 = tiles sharing the activations through LDS, 4 = prefill GEMM on tile-major weights;
+                                    epilogue 0 LM head, 1 residual, 2 SwiGLU, 3 QKV */
 };
 /* Copies internal state to HOST memory as fp32 / int32.  Synchronises.  n_tokens limits KV reads. */
 int eesd_debug_read(eesd_ctx* ctx, int what, int index, int32_t n_tokens, void* host_dst, size_t bytes);
@@ -312,7 +313,8 @@ int eesd_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
  * process, are not synchronised with running calls and are meant for single-threaded sweeps only (0, or -1 for
  * "fuse_norm", restores the built-in heuristic):
  * "valu_nw", "valu_tpw", "valu_rp", "mfma_nw", "mfma_ksplit", "fuse_norm", "mfma_tile", "tile_kc", "tile_nwt", "pf_kc",
- * "attn_split", "mfma_min_m", "nw_plain", "nw_resid", "nw_swiglu", "nw_qkv" (waves per workgroup of the per-tile
+ * "pf_rows" (rows of a prefill block on tile-major weights, 128 / 256 / 512; read by eesd_create), "pf_ts", "pf_nbw" (tile slots per
+ * workgroup and 16-token blocks per wave of the prefill GEMM), "attn_split", "mfma_min_m", "nw_plain", "nw_resid", "nw_swiglu", "nw_qkv" (waves per workgroup of the per-tile
  * product by epilogue). */
 int eesd_set_tunable(const char* name, int value);
 
@@ -334,8 +336,8 @@ int eesd_op_accept_logits(const void* p_logits, int32_t logits_bf16, float* p_ro
 int eesd_op_softmax_sample(const float* logits, float* probs, int32_t vocab, float temperature, double u,
                            void* hip_stream, int32_t* token);
 /* Y[m][r] = sum_k X[m][k] W[r][k]: the weight-streaming product of the draft (M = 1), verify
- * (M = K+1 <= 16) and prefill (M <= 128, bf16 MFMA family, out % 64 == 0, in % 256 == 0) passes
- * without prologue or epilogue.  W: DEVICE [out][in] in dtype (weight_layout EESD_WEIGHTS_TILED:
+ * (M = K+1 <= 16) and prefill (bf16 MFMA family, in % 256 == 0: M <= 128 with out % 64 == 0 on row-major weights,
+ * M <= 512 with out % 16 == 0 on tile-major weights) passes without prologue or epilogue.  W: DEVICE [out][in] in dtype (weight_layout EESD_WEIGHTS_TILED:
  * packed with kind EESD_PACK_PLAIN); X: DEVICE fp32 [M][in]; Y: DEVICE fp32 [M][out]; path: EESD_GEMM_*.
  * The bf16 path stages the activation rows in one buffer per process: calls that overlap on the GPU race. */
 int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in,

@@ -348,8 +348,8 @@ class EESD:
         return self._read(READ_VERIFY_PROBS, row, 0, np.empty(self.vocab, np.float32))
 
     def launch_counts(self) -> np.ndarray:
-        """[kernel][epilogue] launches: kernel 0 VALU, 1 per-tile, 2 per-group, 3 LDS-shared tiles; epilogue 0 head, 1 residual, 2 SwiGLU, 3 QKV."""
-        return self._read(READ_LAUNCH_COUNTS, 0, 0, np.empty(16, np.int32)).reshape(4, 4)
+        """[kernel][epilogue] launches: kernel 0 VALU, 1 per-tile, 2 per-group, 3 LDS-shared tiles, 4 prefill GEMM; epilogue 0 head, 1 residual, 2 SwiGLU, 3 QKV."""
+        return self._read(READ_LAUNCH_COUNTS, 0, 0, np.empty(20, np.int32)).reshape(5, 4)
 
     def kv(self, cache: int, n_tokens: int):
         sh = self.shape

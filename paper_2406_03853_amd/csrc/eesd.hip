@@ -26,7 +26,8 @@
 #define H_ROWS_AT 4
 #define H_TOKS_AT 24
 #define H_THETA_AT 44
-#define PREFILL_ROWS 128  // rows of a prefill block when the tiled MFMA product applies
+#define PREFILL_ROWS 128  // rows of a prefill block when the tiled MFMA product applies (row-major weights)
+#define PREFILL_ROWS_WIDE 512   // the same on tile-major weights (gemm_pf_kernel)
 
 // ---------------------------------------------------------------------------------------------
 // tunables (benchmark sweeps)
@@ -42,6 +43,9 @@ static int g_tile_nwt = 0;     // 4 / 8: tiles per workgroup of the tile kernel 
 static int g_fuse_norm = -1;   // residual -> next product hand-over without resid_norm_kernel: 1 both products, 2 attention output only, 3 FFN down only, 0 off, -1 by model width
 static int g_nw_epi[4] = {0, 0, 0, 0};   // waves per workgroup of the per-tile product by epilogue (plain, resid, swiglu, qkv)
 static int g_pf_kc = 0;        // 256: prefill blocks take 256-column chunks (default 128)
+static int g_pf_rows = 0;      // rows of a prefill block on tile-major weights: 128 (gemm_tile_kernel), 256 or 512 (gemm_pf_kernel; 0 = 512), read by eesd_create
+static int g_pf_ts = 0;        // gemm_pf_kernel: tile slots per workgroup for one-tile-per-group matrices (4 or 7; 0 = by tile count)
+static int g_pf_nbw = 0;       // gemm_pf_kernel: 16-token blocks per wave (1, 2, 4; 0 = by rows and grid size)
 static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: by rows and tile count
 static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
 
@@ -49,7 +53,7 @@ extern "C" int eesd_set_tunable(const char* name, int value) {
     if (!name) return EESD_EINVAL;
     struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
                                              {"mfma_ksplit", &g_mfma_ksplit}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
-                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
+                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"pf_rows", &g_pf_rows}, {"pf_ts", &g_pf_ts}, {"pf_nbw", &g_pf_nbw}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
     for (auto& e : t)
         if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
     return EESD_EINVAL;
@@ -132,11 +136,14 @@ struct eesd_ctx {
     float *h_t, *cali_u, *theta_dev;      // H_t^(T) [d], W^i H_t^(T) [d], theta_M
     bf16_t* h_tb;                         // bf16 copy of h_t (operand of the MFMA product)
     float* hn_rows;                       // verify_reuse: layer-N hidden state of every draft step's input row [k_cap][d]
-    int launch_counts[16];   // product launches since creation, [kernel 0 VALU / 1 one workgroup per tile / 2 one workgroup per row group / 3 LDS-shared tiles][epilogue]
+    int launch_counts[20];   // product launches since creation, [kernel 0 VALU / 1 one workgroup per tile / 2 one workgroup per row group / 3 LDS-shared tiles / 4 prefill GEMM][epilogue]
     int max_splits;
     int n_cu;              // compute units of the device (fixes the row groups of the tile-major weight layout)
     int ssq_slots;         // partial sums of squares a residual product leaves per row
-    int row_cap;           // rows the activation buffers hold (16, or PREFILL_ROWS)
+    int row_cap;           // rows the activation buffers hold (16, PREFILL_ROWS, or up to PREFILL_ROWS_WIDE with pf_wide)
+    int part_rows;         // rows of one slab of the K-split partial sums
+    bf16_t* xp;            // pf_wide: the input rows of a prefill block's product in operand order (pack_act_kernel)
+    bool pf_wide;          // prefill blocks go through gemm_pf_kernel (tile-major weights, every reduction a multiple of 256)
     hipEvent_t ev[4];
 
     // per-kernel timing of one class of product launches (benchmark hook)
@@ -300,8 +307,65 @@ static hipError_t launch_group(const GemmP& p, hipStream_t st) {
     return hipGetLastError();
 }
 
+// prefill blocks on tile-major weights: 8 waves x 16 NBW tokens against TS tile slots per workgroup
+template <int EPI, int TS, int NBW>
+static hipError_t launch_pf_t(const GemmP& p, int tg, int gx, hipStream_t st) {
+    const size_t lds = (size_t)2 * PF_QC * TS * 1024;
+    auto fn = gemm_pf_kernel<EPI, TS, NBW>;
+    hipError_t e = allow_lds((const void*)fn, lds);
+    if (e != hipSuccess) return e;
+    const int gy = (p.M + PF_NW * 16 * NBW - 1) / (PF_NW * 16 * NBW);
+    hipLaunchKernelGGL(fn, dim3(gx, gy), dim3(64 * PF_NW), lds, st, p, tg);
+    return hipGetLastError();
+}
+template <int EPI, int TS>
+static hipError_t launch_pf_ts(const GemmP& p, int tg, int gx, int nbw, hipStream_t st) {
+    if (nbw == 1) return launch_pf_t<EPI, TS, 1>(p, tg, gx, st);
+    if (nbw == 2) return launch_pf_t<EPI, TS, 2>(p, tg, gx, st);
+    if constexpr (TS <= 4) {   // 7 tile slots x 4 token blocks would not fit the register file
+        if (nbw == 4) return launch_pf_t<EPI, TS, 4>(p, tg, gx, st);
+    }
+    return hipErrorInvalidValue;
+}
+static bool pf_shape_ok(const GemmP& p) { return p.w_packed && p.in_dim % (32 * PF_QC) == 0 && p.M <= PREFILL_ROWS_WIDE && !p.y_partial && !p.ssq_in && !p.xb_out; }
+// xp: room for the block's rows in operand order (ceil(M / 16) * 16 * in_dim elements)
 template <int EPI>
-static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st, int* kernel_taken = nullptr) {
+static hipError_t launch_pf(const GemmP& p_rows, bf16_t* xp, int n_cu, hipStream_t st) {
+    if (!pf_shape_ok(p_rows) || !xp) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(pack_act_kernel, dim3((p_rows.in_dim / 8 + 255) / 256, (p_rows.M + 15) / 16), dim3(256), 0, st, (const bf16_t*)p_rows.X, p_rows.ldx,
+                       p_rows.M, p_rows.in_dim, xp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    GemmP p = p_rows;
+    p.X = xp;
+    const int n_tiles16 = p.out_rows / 16;
+    int tg = 1, ts = 4;
+    if (p.n_groups != n_tiles16) {
+        // one row group per CU: 3 tiles per group - one group per workgroup; 1, 2 or 4 - four tile slots
+        const int units = p.out_rows / 4, max_units = (units + p.n_groups - 1) / p.n_groups;
+        tg = (max_units * 4 + 15) / 16;
+        if (tg > GRP_MAX_TILES) return hipErrorInvalidValue;
+        ts = tg == 3 ? 3 : 4;
+    } else {
+        // one tile per group: 7 tiles per workgroup when there are very many (gate/up: 3584 = 2 x 256 x 7 at the 70B shape)
+        ts = g_pf_ts ? g_pf_ts : (EPI == EPI_SWIGLU && n_tiles16 >= 4 * n_cu ? 7 : 4);
+        if (ts != 4 && (ts != 7 || EPI != EPI_SWIGLU)) return hipErrorInvalidValue;
+    }
+    const int gx = (p.n_groups + ts / tg - 1) / (ts / tg);
+    // tokens per wave: as many as the block has, fewer while the grid would leave CUs without a workgroup
+    int nbw = p.M <= 128 ? 1 : (p.M <= 256 ? 2 : 4);
+    if (ts == 7) nbw = std::min(nbw, 2);
+    while (nbw > 1 && gx * ((p.M + 128 * nbw - 1) / (128 * nbw)) < n_cu) nbw >>= 1;
+    if (g_pf_nbw) nbw = std::min(g_pf_nbw, ts == 7 ? 2 : 4);
+    if (ts == 3) return launch_pf_ts<EPI, 3>(p, tg, gx, nbw, st);
+    if constexpr (EPI == EPI_SWIGLU) {
+        if (ts == 7) return launch_pf_ts<EPI, 7>(p, tg, gx, nbw, st);
+    }
+    return launch_pf_ts<EPI, 4>(p, tg, gx, nbw, st);
+}
+
+template <int EPI>
+static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st, int* kernel_taken = nullptr, int n_cu = 0, bf16_t* xp = nullptr) {
     int taken_dummy;
     int& taken = kernel_taken ? *kernel_taken : taken_dummy;
     taken = 3;
@@ -312,6 +376,7 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st, int* k
     // per workgroup when there are very many.  Prefill blocks (M > 16) always take the tile kernel.
     const int n_tiles16 = p.out_rows / 16;
     const bool partial = EPI == EPI_RESID && p.y_partial;
+    if (p.M > 16 && n_cu > 0 && xp && g_pf_rows != 128 && pf_shape_ok(p)) { taken = 4; return launch_pf<EPI>(p, xp, n_cu, st); }
     if (p.w_packed && p.n_groups != n_tiles16) {
         // one row group per CU: decoding blocks take the group kernel, prefill blocks the tile kernel with a wave per tile of the group
         if (p.M <= 16) { taken = 2; return launch_group<EPI>(p, st); }
@@ -404,7 +469,7 @@ static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
         pm.w_packed = c->cfg.weight_layout == EESD_WEIGHTS_TILED;
         pm.n_groups = pm.w_packed ? pack_n_groups(pm.out_rows, c->n_cu) : 0;
         int taken = 0;
-        HIP_TRY(c, launch_mfma<EPI>(pm, ksplit, c->stream, &taken));
+        HIP_TRY(c, launch_mfma<EPI>(pm, ksplit, c->stream, &taken, c->n_cu, c->xp));
         ++c->launch_counts[taken * 4 + EPI];
     } else {
         HIP_TRY(c, launch_valu<EPI>(p, is_bf16(c), c->stream));
@@ -522,7 +587,7 @@ static void fill_qkv(eesd_ctx* c, GemmP& p, int cache, int pos0, int head0) {
 
 static int launch_resid_norm(eesd_ctx* c, int M, int ksplit, const void* gain) {
     const int d = c->cfg.d_model;
-    hipLaunchKernelGGL((resid_norm_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->stream, c->x, d, c->part, ksplit, c->row_cap, d, (const bf16_t*)gain,
+    hipLaunchKernelGGL((resid_norm_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->stream, c->x, d, c->part, ksplit, c->part_rows, d, (const bf16_t*)gain,
                        c->cfg.rms_eps, d, c->xb, d);
     HIP_TRY(c, hipGetLastError());
     return EESD_OK;
@@ -554,14 +619,20 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
         if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
         if ((rc = launch_attention(c, cache, M, pos0, true))) return rc;
         p = gemm_base(lw.wo, c->ab, qd, M, d, qd);
-        if (fused_wo) {
+        const bool gemm_blk = M > MAX_ROWS && c->pf_wide;   // prefill block: the product adds into the stream, a norm kernel follows
+        if (gemm_blk) {
+            p.Y = c->x; p.ldy = d;
+            if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
+            if ((rc = launch_resid_norm(c, M, 0, lw.ffn_norm))) return rc;
+            c->xb_has_ssq = false;
+        } else if (fused_wo) {
             p.Y = c->x; p.ldy = d;
             fuse_next(c, p, lw.ffn_norm);
             if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
             c->xb_has_ssq = true;
         } else {
             int ks = mfma_ksplit(d, qd);
-            p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->row_cap;
+            p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->part_rows;
             if ((rc = gemm_launch<EPI_RESID>(c, true, p, ks))) return rc;
             if ((rc = launch_resid_norm(c, M, ks, lw.ffn_norm))) return rc;
             c->xb_has_ssq = false;
@@ -571,14 +642,19 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
         take_xb(c, p);
         if ((rc = gemm_launch<EPI_SWIGLU>(c, true, p))) return rc;
         p = gemm_base(lw.w_down, c->actb, f, M, d, f);
-        if (fused_down) {
+        if (gemm_blk) {
+            p.Y = c->x; p.ldy = d;
+            if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
+            if ((rc = launch_resid_norm(c, M, 0, next_gain))) return rc;
+            c->xb_has_ssq = false;
+        } else if (fused_down) {
             p.Y = c->x; p.ldy = d;
             fuse_next(c, p, next_gain);
             if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
             c->xb_has_ssq = true;
         } else {
             int ks = mfma_ksplit(d, f);
-            p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->row_cap;
+            p.Y = c->part; p.ldy = d; p.y_partial = 1; p.part_rows = c->part_rows;
             if ((rc = gemm_launch<EPI_RESID>(c, true, p, ks))) return rc;
             if ((rc = launch_resid_norm(c, M, ks, next_gain))) return rc;
             c->xb_has_ssq = false;
@@ -895,7 +971,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
-                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb, c->hn_rows};
+                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->xp, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb, c->hn_rows};
     for (void* p : dev)
         if (p) hipFree(p);
     if (c->h_table) hipHostFree(c->h_table);
@@ -959,7 +1035,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->kv_pool = nullptr; c->d_table = nullptr; c->h_table = nullptr;
     c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = c->part = c->ssq = nullptr;
     c->xb_has_ssq = false;
-    c->xb = c->ab = c->actb = nullptr;
+    c->xb = c->ab = c->actb = c->xp = nullptr;
     c->blk_tok = c->prompt_dev = c->result_dev = c->tree_blk = nullptr;
     c->h_t = c->cali_u = c->theta_dev = nullptr; c->h_tb = nullptr; c->hn_rows = nullptr;
     c->cali_set = false; memset(&c->cali, 0, sizeof c->cali);
@@ -1011,6 +1087,11 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
         bool tiled = g.dtype == EESD_DTYPE_BF16 && g.gemm_path != EESD_GEMM_VALU && tile_shape_ok(qkv_rows, d) && tile_shape_ok(kv_rows, d) &&
                      tile_shape_ok(d, qd) && tile_shape_ok(2 * f, d) && tile_shape_ok(d, f) && tile_shape_ok(V, d);
         c->row_cap = tiled ? PREFILL_ROWS : MAX_ROWS;
+        const int chunk = 32 * PF_QC;
+        c->pf_wide = g.dtype == EESD_DTYPE_BF16 && g.gemm_path != EESD_GEMM_VALU && g.weight_layout == EESD_WEIGHTS_TILED && g_pf_rows != 128 &&
+                     d % chunk == 0 && qd % chunk == 0 && f % chunk == 0 && d % 16 == 0 && f % 8 == 0;
+        if (c->pf_wide) c->row_cap = g_pf_rows == 256 ? 256 : PREFILL_ROWS_WIDE;
+        c->part_rows = std::min(c->row_cap, PREFILL_ROWS);
     }
     const size_t R = c->row_cap;
     if ((rc = dev_alloc(c, &c->x, R * d))) return bail(rc);
@@ -1023,9 +1104,10 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if ((rc = dev_alloc(c, &c->q_rows, (size_t)g.k_cap * V))) return bail(rc);
     if ((rc = dev_alloc(c, &c->part_o, (size_t)MAX_ROWS * g.n_heads * c->max_splits * g.head_dim))) return bail(rc);
     if ((rc = dev_alloc(c, &c->part_ml, (size_t)MAX_ROWS * g.n_heads * c->max_splits * 2))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->part, (size_t)MFMA_MAX_KSPLIT * R * d))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->part, (size_t)MFMA_MAX_KSPLIT * c->part_rows * d))) return bail(rc);
     if ((rc = dev_alloc(c, &c->ssq, (size_t)c->ssq_slots * MAX_ROWS))) return bail(rc);
     hipMemset(c->ssq, 0, sizeof(float) * c->ssq_slots * MAX_ROWS);
+    if (c->pf_wide && (rc = dev_alloc(c, &c->xp, R * std::max(std::max(d, qd), f)))) return bail(rc);
     if ((rc = dev_alloc(c, &c->xb, R * d))) return bail(rc);
     if ((rc = dev_alloc(c, &c->ab, R * qd))) return bail(rc);
     if ((rc = dev_alloc(c, &c->actb, R * f))) return bail(rc);
@@ -1805,8 +1887,11 @@ extern "C" int eesd_pack_weight(const void* src, void* dst, int32_t out_rows, in
 
 extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, int32_t out, int32_t in, int32_t dtype, int32_t path,
                             int32_t weight_layout, void* hip_stream) {
-    if (!W || !X || !Y || M < 1 || M > PREFILL_ROWS || out < 2 || in < 8) return EESD_EINVAL;
+    if (!W || !X || !Y || M < 1 || out < 2 || in < 8) return EESD_EINVAL;
     if (weight_layout != EESD_WEIGHTS_ROW_MAJOR && weight_layout != EESD_WEIGHTS_TILED) return EESD_EINVAL;
+    // blocks of more than 128 rows exist on tile-major weights only (gemm_pf_kernel)
+    const bool wide = weight_layout == EESD_WEIGHTS_TILED && in % (32 * PF_QC) == 0 && g_pf_rows != 128;
+    if (M > (wide ? PREFILL_ROWS_WIDE : PREFILL_ROWS)) return EESD_EINVAL;
     if (weight_layout == EESD_WEIGHTS_TILED && (dtype != EESD_DTYPE_BF16 || path == EESD_GEMM_VALU)) return EESD_EINVAL;
     if (dtype != EESD_DTYPE_F32 && dtype != EESD_DTYPE_BF16) return EESD_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -1823,7 +1908,7 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
         static size_t xb_elems = 0;
         static std::mutex mu;      // guards the growth; calls that overlap on the GPU still share the rows (see the header)
         std::lock_guard<std::mutex> lock(mu);
-        const size_t need = (size_t)PREFILL_ROWS * in;
+        const size_t need = (size_t)2 * PREFILL_ROWS_WIDE * in;     // the rows, and the same in operand order for blocks of more than 16
         if (need > xb_elems) {
             if (hipDeviceSynchronize() != hipSuccess) return EESD_EDEVICE;
             if (xb) hipFree(xb);
@@ -1832,6 +1917,7 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
             if (hipMemset(xb, 0, need * sizeof(bf16_t)) != hipSuccess) return EESD_EDEVICE;
             xb_elems = need;
         }
+        bf16_t* xp = xb + (size_t)PREFILL_ROWS_WIDE * in;
         hipLaunchKernelGGL(to_bf16_kernel, dim3((in + 255) / 256, M), dim3(256), 0, st, X, in, in, xb, in);
         hipError_t e = hipGetLastError();
         if (e == hipSuccess) {
@@ -1839,7 +1925,7 @@ extern "C" int eesd_op_gemm(const void* W, const float* X, float* Y, int32_t M, 
             p.Y = Y; p.ldy = out;
             p.w_packed = weight_layout == EESD_WEIGHTS_TILED;
             p.n_groups = n_groups;
-            e = launch_mfma<EPI_PLAIN>(p, 1, st);
+            e = launch_mfma<EPI_PLAIN>(p, 1, st, nullptr, device_cu_count(), xp);
         }
         return e == hipSuccess ? EESD_OK : EESD_EDEVICE;
     }

@@ -36,12 +36,13 @@ def _round_parity(o, g, ks, tol):
 
 
 @pytest.mark.parametrize("name,n_prompt,ks,tiled", [("13b", 150, (10, 3), 0), ("70b", 40, (7,), 0), ("13b", 150, (10, 3), 1), ("70b", 140, (7, 2), 1),
-                                                    ("70b", 140, (10, 15), 1)])
+                                                    ("70b", 140, (10, 15), 1), ("13b", 530, (3,), 1), ("70b", 530, (2,), 1)])
 def test_full_width_reduced_depth_matches_oracle(name, n_prompt, ks, tiled):
-    """tiled = 1: the weights in the tile-major layout the benchmark runs with.  The last case is the block of
+    """tiled = 1: the weights in the tile-major layout the benchmark runs with.  The fifth case is the block of
     11 and 16 rows on the 70B shape, where the gate/up product and the LM head leave the one-workgroup-per-tile
-    kernel for the one whose tiles share the activations through LDS (8 and 4 tiles per workgroup); the launch
-    counters prove which kernels really ran."""
+    kernel for the one whose tiles share the activations through LDS (8 and 4 tiles per workgroup); the last two
+    prefill a whole 512-token block and a ragged one of 18 through the prefill GEMM (every row of all three
+    caches is compared below); the launch counters prove which kernels really ran."""
     require_gpu()
     base = si.LLAMA13B if name == "13b" else si.LLAMA70B
     shape = si.reduced_depth(base, 2, 1)
@@ -52,6 +53,10 @@ def test_full_width_reduced_depth_matches_oracle(name, n_prompt, ks, tiled):
     assert rel_err(g.verify_logits(0), o.prefill_logits) < TOL_BF16
     g.force_pending(t_ref)
     before = g.launch_counts()
+    if tiled:
+        # prefill blocks (all of more than 16 rows here) on tile-major weights: the prefill GEMM (kernel 4) and nothing else
+        nb, L = (n_prompt + 511) // 512, shape["n_layers"]
+        assert before[4].tolist() == [0, 2 * L * nb, L * nb, (L + 1) * nb] and before[3].sum() == 0 and before[2].sum() == 0
     _round_parity(o, g, ks, TOL_BF16)
     n = o.kv_len
     for cache in range(3):

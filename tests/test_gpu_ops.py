@@ -118,6 +118,38 @@ def test_gemm_tiled_weight_layout_equals_row_major(M, out, inn):
     assert np.max(np.abs(Y1.cpu().numpy() - ref)) / np.max(np.abs(ref)) < TOL_BF16
 
 
+@pytest.mark.parametrize("M", [17, 100, 256, 300, 512])
+@pytest.mark.parametrize("out,inn", [(1024, 512), (8192, 2048), (10240, 1024), (15360, 1024), (5120, 13824), (27648, 512)])
+def test_prefill_gemm_on_tile_major_weights(M, out, inn):
+    """Blocks of more than 16 rows on tile-major weights (the prefill GEMM: weight operands shared through LDS,
+    the block's rows read in operand order).  On a 256-CU device the shapes give one tile per row group (1024,
+    27648), groups of 2 tiles (8192), 3 (10240: 40 rows), 4 (15360: 60 rows) and of 20 rows (5120: a whole tile
+    and a quarter); the row counts give 1, 2 and 4 token blocks per wave, idle waves, and a ragged last block."""
+    require_gpu()
+    pk = _pk()
+    g = torch.Generator(device="cpu").manual_seed(out + inn + M)
+    W = (torch.randn(out, inn, generator=g) * 0.05).to(torch.bfloat16)
+    X = torch.randn(M, inn, generator=g)
+    Y = torch.full((M, out), float("nan"), device="cuda")
+    pk.op_gemm(pk.pack_weight(W.cuda()), X.cuda(), Y, pk.GEMM_MFMA, weight_layout=pk.WEIGHTS_TILED)
+    torch.cuda.synchronize()
+    ref = X.double().numpy() @ W.double().numpy().T
+    assert rel_err(Y.cpu().numpy(), ref) < TOL_BF16
+    # against the rows as the kernel sees them (rounded to bf16): only the order of the fp32 sums differs
+    ref16 = X.to(torch.bfloat16).double().numpy() @ W.double().numpy().T
+    assert rel_err(Y.cpu().numpy(), ref16) < 1e-5
+    if M <= 128:
+        # the kernel that row-major weights (and pf_rows = 128) take for such blocks agrees
+        Y0 = torch.empty(M, out, device="cuda")
+        try:
+            pk.set_tunable("pf_rows", 128)
+            pk.op_gemm(pk.pack_weight(W.cuda()), X.cuda(), Y0, pk.GEMM_MFMA, weight_layout=pk.WEIGHTS_TILED)
+            torch.cuda.synchronize()
+        finally:
+            pk.set_tunable("pf_rows", 0)
+        assert float((Y0 - Y).abs().max()) <= 2e-5 * float(Y.abs().max())
+
+
 def test_pack_weight_is_a_permutation_of_16_byte_pieces():
     require_gpu()
     pk = _pk()
