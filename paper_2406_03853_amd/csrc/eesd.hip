@@ -142,7 +142,7 @@ struct eesd_ctx {
     int ssq_slots;         // partial sums of squares a residual product leaves per row
     int row_cap;           // rows the activation buffers hold (16, PREFILL_ROWS, or up to PREFILL_ROWS_WIDE with pf_wide)
     int part_rows;         // rows of one slab of the K-split partial sums
-    bf16_t* xp;            // pf_wide: the input rows of a prefill block's product in operand order (pack_act_kernel)
+    bf16_t *xpb, *abp, *actp;   // pf_wide: what xb, ab and actb hold for a prefill block, in operand order (written by the producers)
     bool pf_wide;          // prefill blocks go through gemm_pf_kernel (tile-major weights, every reduction a multiple of 256)
     hipEvent_t ev[4];
 
@@ -328,16 +328,18 @@ static hipError_t launch_pf_ts(const GemmP& p, int tg, int gx, int nbw, hipStrea
     return hipErrorInvalidValue;
 }
 static bool pf_shape_ok(const GemmP& p) { return p.w_packed && p.in_dim % (32 * PF_QC) == 0 && p.M <= PREFILL_ROWS_WIDE && !p.y_partial && !p.ssq_in && !p.xb_out; }
-// xp: room for the block's rows in operand order (ceil(M / 16) * 16 * in_dim elements)
+// p.X: the block's rows in operand order (x_packed), or row-major, then xp: room for them in operand order (ceil(M / 16) * 16 * in_dim elements)
 template <int EPI>
 static hipError_t launch_pf(const GemmP& p_rows, bf16_t* xp, int n_cu, hipStream_t st) {
-    if (!pf_shape_ok(p_rows) || !xp) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(pack_act_kernel, dim3((p_rows.in_dim / 8 + 255) / 256, (p_rows.M + 15) / 16), dim3(256), 0, st, (const bf16_t*)p_rows.X, p_rows.ldx,
-                       p_rows.M, p_rows.in_dim, xp);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (!pf_shape_ok(p_rows) || (!xp && !p_rows.x_packed)) return hipErrorInvalidValue;
     GemmP p = p_rows;
-    p.X = xp;
+    if (!p.x_packed) {
+        hipLaunchKernelGGL(pack_act_kernel, dim3((p.in_dim / 8 + 255) / 256, (p.M + 15) / 16), dim3(256), 0, st, (const bf16_t*)p.X, p.ldx, p.M, p.in_dim, xp);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        p.X = xp;
+        p.x_packed = 1;
+    }
     const int n_tiles16 = p.out_rows / 16;
     int tg = 1, ts = 4;
     if (p.n_groups != n_tiles16) {
@@ -376,7 +378,7 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st, int* k
     // per workgroup when there are very many.  Prefill blocks (M > 16) always take the tile kernel.
     const int n_tiles16 = p.out_rows / 16;
     const bool partial = EPI == EPI_RESID && p.y_partial;
-    if (p.M > 16 && n_cu > 0 && xp && g_pf_rows != 128 && pf_shape_ok(p)) { taken = 4; return launch_pf<EPI>(p, xp, n_cu, st); }
+    if (p.M > 16 && n_cu > 0 && (xp || p.x_packed) && g_pf_rows != 128 && pf_shape_ok(p)) { taken = 4; return launch_pf<EPI>(p, xp, n_cu, st); }
     if (p.w_packed && p.n_groups != n_tiles16) {
         // one row group per CU: decoding blocks take the group kernel, prefill blocks the tile kernel with a wave per tile of the group
         if (p.M <= 16) { taken = 2; return launch_group<EPI>(p, st); }
@@ -469,7 +471,7 @@ static int gemm_launch(eesd_ctx* c, bool mfma, const GemmP& p, int ksplit = 1) {
         pm.w_packed = c->cfg.weight_layout == EESD_WEIGHTS_TILED;
         pm.n_groups = pm.w_packed ? pack_n_groups(pm.out_rows, c->n_cu) : 0;
         int taken = 0;
-        HIP_TRY(c, launch_mfma<EPI>(pm, ksplit, c->stream, &taken, c->n_cu, c->xp));
+        HIP_TRY(c, launch_mfma<EPI>(pm, ksplit, c->stream, &taken, c->n_cu, nullptr));
         ++c->launch_counts[taken * 4 + EPI];
     } else {
         HIP_TRY(c, launch_valu<EPI>(p, is_bf16(c), c->stream));
@@ -540,6 +542,10 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
     a.scale = 1.0f / sqrtf((float)g.head_dim);
     a.out = out_bf16 ? (void*)c->ab : (void*)c->attn;
     a.out_bf16 = out_bf16;
+    if (out_bf16 && M > MAX_ROWS && c->pf_wide) {   // prefill block: the output product reads its rows in operand order
+        a.out = c->abp;
+        a.out_packed = 1;
+    }
     a.part_o = c->part_o; a.part_ml = c->part_ml;
     if (c->tree_active) {
         a.tree = 1;
@@ -567,8 +573,9 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
 static int launch_rmsnorm_bf16(eesd_ctx* c, const float* x, int M, const void* gain, bf16_t* out, int ld) {
     int d = c->cfg.d_model;
     if (out == c->xb) c->xb_has_ssq = false;
+    bf16_t* xp = (out == c->xb && M > MAX_ROWS && c->pf_wide) ? c->xpb : nullptr;    // prefill block: its GEMMs read the rows in operand order
     hipLaunchKernelGGL((rmsnorm_bf16_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->stream, x, d, (const bf16_t*)gain, c->cfg.rms_eps, d,
-                       out, ld);
+                       out, ld, xp);
     HIP_TRY(c, hipGetLastError());
     return EESD_OK;
 }
@@ -587,8 +594,9 @@ static void fill_qkv(eesd_ctx* c, GemmP& p, int cache, int pos0, int head0) {
 
 static int launch_resid_norm(eesd_ctx* c, int M, int ksplit, const void* gain) {
     const int d = c->cfg.d_model;
+    bf16_t* xp = (M > MAX_ROWS && c->pf_wide) ? c->xpb : nullptr;
     hipLaunchKernelGGL((resid_norm_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->stream, c->x, d, c->part, ksplit, c->part_rows, d, (const bf16_t*)gain,
-                       c->cfg.rms_eps, d, c->xb, d);
+                       c->cfg.rms_eps, d, c->xb, d, xp);
     HIP_TRY(c, hipGetLastError());
     return EESD_OK;
 }
@@ -613,13 +621,17 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
         const bool grouped = c->cfg.weight_layout == EESD_WEIGHTS_TILED && pack_n_groups(d, c->n_cu) != d / 16;
         const bool fused_wo = fuse_ok && (grouped || g_fuse_norm < 0 ? true : (g_fuse_norm == 1 || g_fuse_norm == 2));
         const bool fused_down = fuse_ok && (grouped || (g_fuse_norm < 0 ? d / 16 >= 448 : (g_fuse_norm == 1 || g_fuse_norm == 3)));
+        // prefill block on tile-major weights: GEMMs whose inputs the producers leave in operand order; a residual product
+        // adds into the stream and a norm kernel follows
+        const bool gemm_blk = M > MAX_ROWS && c->pf_wide;
         GemmP p = gemm_base(lw.wqkv, c->xb, d, M, qkv_rows, d);
         fill_qkv(c, p, cache, pos0, 0);
         take_xb(c, p);
+        if (gemm_blk) { p.X = c->xpb; p.x_packed = 1; }
         if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
         if ((rc = launch_attention(c, cache, M, pos0, true))) return rc;
         p = gemm_base(lw.wo, c->ab, qd, M, d, qd);
-        const bool gemm_blk = M > MAX_ROWS && c->pf_wide;   // prefill block: the product adds into the stream, a norm kernel follows
+        if (gemm_blk) { p.X = c->abp; p.x_packed = 1; }
         if (gemm_blk) {
             p.Y = c->x; p.ldy = d;
             if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
@@ -640,8 +652,10 @@ static int run_layer(eesd_ctx* c, const eesd_layer_weights& lw, int cache, int M
         p = gemm_base(lw.w_gate_up, c->xb, d, M, 2 * f, d);
         p.Y = c->actb; p.ldy = f; p.y_bf16 = 1;
         take_xb(c, p);
+        if (gemm_blk) { p.X = c->xpb; p.x_packed = 1; p.Y = c->actp; p.y_packed = 1; }
         if ((rc = gemm_launch<EPI_SWIGLU>(c, true, p))) return rc;
         p = gemm_base(lw.w_down, c->actb, f, M, d, f);
+        if (gemm_blk) { p.X = c->actp; p.x_packed = 1; }
         if (gemm_blk) {
             p.Y = c->x; p.ldy = d;
             if ((rc = gemm_launch<EPI_RESID>(c, true, p))) return rc;
@@ -696,6 +710,7 @@ static int run_ee_kv_fill(eesd_ctx* c, int M, int pos0, bool mfma) {
         fill_qkv(c, p, g.n_layers, pos0, 0);
         p.head_min = g.n_heads;
         take_xb(c, p);
+        if (M > MAX_ROWS && c->pf_wide) { p.X = c->xpb; p.x_packed = 1; }
         if ((rc = gemm_launch<EPI_QKV>(c, true, p))) return rc;
     } else if (mfma) {
         GemmP p = gemm_base(wkv, c->xb, d, M, rows, d);
@@ -971,7 +986,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
-                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->xp, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb, c->hn_rows};
+                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->xpb, c->abp, c->actp, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb, c->hn_rows};
     for (void* p : dev)
         if (p) hipFree(p);
     if (c->h_table) hipHostFree(c->h_table);
@@ -1035,7 +1050,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->kv_pool = nullptr; c->d_table = nullptr; c->h_table = nullptr;
     c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = c->part = c->ssq = nullptr;
     c->xb_has_ssq = false;
-    c->xb = c->ab = c->actb = c->xp = nullptr;
+    c->xb = c->ab = c->actb = c->xpb = c->abp = c->actp = nullptr;
     c->blk_tok = c->prompt_dev = c->result_dev = c->tree_blk = nullptr;
     c->h_t = c->cali_u = c->theta_dev = nullptr; c->h_tb = nullptr; c->hn_rows = nullptr;
     c->cali_set = false; memset(&c->cali, 0, sizeof c->cali);
@@ -1107,7 +1122,15 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if ((rc = dev_alloc(c, &c->part, (size_t)MFMA_MAX_KSPLIT * c->part_rows * d))) return bail(rc);
     if ((rc = dev_alloc(c, &c->ssq, (size_t)c->ssq_slots * MAX_ROWS))) return bail(rc);
     hipMemset(c->ssq, 0, sizeof(float) * c->ssq_slots * MAX_ROWS);
-    if (c->pf_wide && (rc = dev_alloc(c, &c->xp, R * std::max(std::max(d, qd), f)))) return bail(rc);
+    if (c->pf_wide) {
+        if ((rc = dev_alloc(c, &c->xpb, R * d))) return bail(rc);
+        if ((rc = dev_alloc(c, &c->abp, R * qd))) return bail(rc);
+        if ((rc = dev_alloc(c, &c->actp, R * f))) return bail(rc);
+        // tokens past a block's last row keep whatever the buffers held: their products are never stored
+        hipMemset(c->xpb, 0, sizeof(bf16_t) * R * d);
+        hipMemset(c->abp, 0, sizeof(bf16_t) * R * qd);
+        hipMemset(c->actp, 0, sizeof(bf16_t) * R * f);
+    }
     if ((rc = dev_alloc(c, &c->xb, R * d))) return bail(rc);
     if ((rc = dev_alloc(c, &c->ab, R * qd))) return bail(rc);
     if ((rc = dev_alloc(c, &c->actb, R * f))) return bail(rc);
