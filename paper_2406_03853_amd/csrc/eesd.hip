@@ -531,9 +531,17 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
         // bf16: one 32-key step per wave while the cache is short (measured 0.5 % of a layer better than two), two beyond
         split_len = std::max(kb ? (n_keys <= 1024 && M <= MAX_ROWS ? 32 : 64) : 2 * ATT_TT, split_len);
     }
+    const int max_splits = std::max(1, std::min(c->max_splits, (MAX_ROWS * c->max_splits) / M));   // partial buffers hold 16 rows x max_splits
+    // prefill blocks: the query tiles of a workgroup share the keys through LDS (attn_pf_kernel); key splits only while
+    // the block alone leaves CUs without a workgroup
+    const bool shared_keys = kb && M > MAX_ROWS && g.kv_page % 32 == 0 && !c->tree_active;
+    if (shared_keys && !g_attn_split) {
+        const int wgs = g.n_kv_heads * ((qtiles + 7) / 8);
+        const int want = std::max(1, std::min(max_splits, (c->n_cu + wgs - 1) / wgs));
+        split_len = std::max(64, (n_keys + want - 1) / want);
+    }
     split_len = (split_len + tile - 1) / tile * tile;
     int n_splits = (n_keys + split_len - 1) / split_len;
-    const int max_splits = std::max(1, std::min(c->max_splits, (MAX_ROWS * c->max_splits) / M));   // partial buffers hold 16 rows x max_splits
     if (n_splits > max_splits) {
         split_len = ((n_keys + max_splits - 1) / max_splits + tile - 1) / tile * tile;
         n_splits = (n_keys + split_len - 1) / split_len;
@@ -554,7 +562,10 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
     if (kb) {
         dim3 grid(n_splits * g.n_kv_heads, (qtiles + 7) / 8);
         const int nwq = std::min(qtiles, 8);
-        if (g.head_dim == 128) hipLaunchKernelGGL((attn_mfma_kernel<128>), grid, dim3(64 * nwq), 0, c->stream, a);
+        if (shared_keys) {
+            if (g.head_dim == 128) hipLaunchKernelGGL((attn_pf_kernel<128>), grid, dim3(512), 0, c->stream, a);
+            else hipLaunchKernelGGL((attn_pf_kernel<64>), grid, dim3(512), 0, c->stream, a);
+        } else if (g.head_dim == 128) hipLaunchKernelGGL((attn_mfma_kernel<128>), grid, dim3(64 * nwq), 0, c->stream, a);
         else hipLaunchKernelGGL((attn_mfma_kernel<64>), grid, dim3(64 * nwq), 0, c->stream, a);
     } else {
         dim3 grid(n_splits * g.n_kv_heads, qtiles);
