@@ -26,6 +26,7 @@ WORKLOADS = {
     "tiny": ("TINY", 0, 32, 64, 5),
 }
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def pass_bytes(shape, n_layers_run, with_head, kv_tokens, si):
@@ -178,6 +179,22 @@ def summarise(stats, shape, n_prompt, max_new, bf16, si):
     return out, mean_k, mean_commit
 
 
+def time_prefill(ctx, torch, prompt, shape, si, reps=3):
+    """eesd_prefill alone (it is part of every timed step): milliseconds, and the rate of its products against the
+    bf16 MFMA peak (2 flop per weight of the L layers and token; attention and the one-row LM head not counted)."""
+    ctx.prefill(prompt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        ctx.prefill(prompt)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / reps * 1e3
+    flops = 2.0 * len(prompt) * shape["n_layers"] * si.layer_param_count(shape)
+    tf = flops / (ms * 1e-3) / 1e12
+    return {"tokens": len(prompt), "ms": ms, "ms_per_layer": ms / shape["n_layers"], "TFLOPs": tf, "bound": "mfma", "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+            "frac": tf / MFMA_BF16_PEAK_TFLOPS}
+
+
 def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperature, tiled, steps):
     """A short untimed-by-the-headline generation run on given weights: tokens/s and per-pass figures."""
     max_seq = (n_prompt + max_new + k_cap + 2 + 63) // 64 * 64
@@ -194,6 +211,8 @@ def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperatu
     passes["tokens_per_s"] = steps * max_new / dt
     passes["steps"] = steps
     passes["temperature"] = temperature
+    if shape["dtype"] == "bf16":
+        passes["prefill"] = time_prefill(ctx, torch, prompts[0], shape, si)
     ctx.close()
     return passes
 
@@ -306,6 +325,8 @@ def main():
 
     passes, mean_k, mean_commit = summarise(stats, shape, n_prompt, max_new, bf16, si)
     passes["weight_init_s"] = t_weights
+    if bf16:
+        passes["prefill"] = time_prefill(ctx, torch, prompts[0], shape, si)
     N, L = shape["n_draft_layers"], shape["n_layers"]
     esz = 2 if bf16 else 4
     kernel_bytes = 2 * shape["d_ff"] * shape["d_model"] * esz          # weights of one gate/up product

@@ -557,7 +557,7 @@ static int launch_attention(eesd_ctx* c, int cache, int M, int pos0, bool out_bf
     a.part_o = c->part_o; a.part_ml = c->part_ml;
     if (c->tree_active) {
         a.tree = 1;
-        memcpy(a.tree_mask, c->tree_mask, sizeof a.tree_mask);
+        for (int r = 0; r < 16; ++r) a.tree_mask[r >> 2] |= (unsigned long long)c->tree_mask[r] << (16 * (r & 3));
     }
     if (kb) {
         dim3 grid(n_splits * g.n_kv_heads, (qtiles + 7) / 8);
@@ -599,7 +599,7 @@ static void fill_qkv(eesd_ctx* c, GemmP& p, int cache, int pos0, int head0) {
     p.kv_bf16 = is_bf16(c);
     if (c->tree_active) {
         p.tree = 1;
-        memcpy(p.rope_off, c->tree_depth, sizeof p.rope_off);
+        for (int r = 0; r < 16; ++r) p.rope_off |= (unsigned long long)(c->tree_depth[r] & 15) << (4 * r);
     }
 }
 
