@@ -388,6 +388,12 @@ def main():
         p13["pass_frac"] = {"draft": p13["draft_step_GBps"] / HBM_PEAK_GBS, "verify": p13["verify_GBps"] / HBM_PEAK_GBS}
         out["passes_13b"] = p13
         out["passes_13b_T0"] = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 0.0, True, 2)
+        # the long-context configuration of the same shape: a 3840-token prompt, the cache grows to 4096
+        _, _, npl, newl, capl = WORKLOADS["13b-long"]
+        pl = side_generation(pk, si, torch, w13, shape13, npl, newl, capl, 1.0, True, 2)
+        pl["workload"] = f"full EESD generation, {shape13['name']}, prompt {npl}, {newl} new tokens, K cap {capl}, temperature 1"
+        pl["pass_frac"] = {"draft": pl["draft_step_GBps"] / HBM_PEAK_GBS, "verify": pl["verify_GBps"] / HBM_PEAK_GBS}
+        out["passes_13b_long"] = pl
     print(json.dumps(out))
 
 
