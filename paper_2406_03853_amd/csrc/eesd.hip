@@ -283,7 +283,9 @@ static hipError_t launch_tile_t(const GemmP& p, int ksplit, hipStream_t st) {
     if (e != hipSuccess) return e;
     const bool grouped = p.w_packed && p.n_groups != p.out_rows / 16;
     if (grouped && NWT < GRP_MAX_TILES) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(grouped ? p.n_groups : p.out_rows / (16 * NWT), ksplit), dim3(64 * NWT), lds, st, p);
+    GemmP pl = p;
+    pl.nw = NWT; pl.ksplit = ksplit;
+    hipLaunchKernelGGL(fn, dim3(grouped ? p.n_groups : p.out_rows / (16 * NWT), ksplit), dim3(64 * NWT), lds, st, pl);
     return hipGetLastError();
 }
 
@@ -297,11 +299,13 @@ static hipError_t launch_group(const GemmP& p, hipStream_t st) {
     const int steps = p.in_dim / 128;
     while (nw > 1 && steps / nw < 2) nw >>= 1;
     const size_t lds = (size_t)nw * tmax * 1024;
+    GemmP pl = p;
+    pl.nw = nw; pl.ksplit = 1;
     switch (tmax) {
-        case 1: hipLaunchKernelGGL((gemm_group_kernel<EPI, 1>), dim3(p.n_groups), dim3(nw * 64), lds, st, p); break;
-        case 2: hipLaunchKernelGGL((gemm_group_kernel<EPI, 2>), dim3(p.n_groups), dim3(nw * 64), lds, st, p); break;
-        case 3: hipLaunchKernelGGL((gemm_group_kernel<EPI, 3>), dim3(p.n_groups), dim3(nw * 64), lds, st, p); break;
-        case 4: hipLaunchKernelGGL((gemm_group_kernel<EPI, 4>), dim3(p.n_groups), dim3(nw * 64), lds, st, p); break;
+        case 1: hipLaunchKernelGGL((gemm_group_kernel<EPI, 1>), dim3(p.n_groups), dim3(nw * 64), lds, st, pl); break;
+        case 2: hipLaunchKernelGGL((gemm_group_kernel<EPI, 2>), dim3(p.n_groups), dim3(nw * 64), lds, st, pl); break;
+        case 3: hipLaunchKernelGGL((gemm_group_kernel<EPI, 3>), dim3(p.n_groups), dim3(nw * 64), lds, st, pl); break;
+        case 4: hipLaunchKernelGGL((gemm_group_kernel<EPI, 4>), dim3(p.n_groups), dim3(nw * 64), lds, st, pl); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -432,7 +436,9 @@ static hipError_t launch_mfma(const GemmP& p, int ksplit, hipStream_t st, int* k
     }
     nw = std::max(1, std::min(nw, 16));
     size_t lds = (size_t)nw * 64 * 16;
-    hipLaunchKernelGGL((gemm_mfma_kernel<EPI>), dim3(n_tiles, ksplit), dim3(nw * 64), lds, st, p);
+    GemmP pl = p;
+    pl.nw = nw; pl.ksplit = ksplit;
+    hipLaunchKernelGGL((gemm_mfma_kernel<EPI>), dim3(n_tiles, ksplit), dim3(nw * 64), lds, st, pl);
     return hipGetLastError();
 }
 
