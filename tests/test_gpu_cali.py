@@ -59,19 +59,20 @@ def test_predictor_scores_match_oracle_under_teacher_forcing(name, temp, tiled):
     assert max(seen) - min(seen) > 0.05
 
 
-@pytest.mark.parametrize("name", list(SHAPES))
-def test_cali_generation_matches_oracle(name):
-    require_gpu()
+def _cali_generation_case(name, seed, first):
+    """One generation under the calibrated controller on both sides; returns whether every decision of the run sat
+    outside the score tolerance (then the K sequence and the posterior must be the oracle's, and that was asserted)."""
     import paper_2406_03853_amd as pk
     shape = SHAPES[name]
     tol = tol_of(shape)
-    o, g = make_pair(shape, 7, 192, 0.0, k_cap=6, gamma=0.05, ts_mode=pk.TS_CALI, seed=4)
+    o, g = make_pair(shape, 7, 192, 0.0, k_cap=6, gamma=0.05, ts_mode=pk.TS_CALI, seed=seed)
     cw_np, cw_gpu = _cali_pair(shape, 2)
     prompt = si.make_prompt(24, shape["vocab"], 0)
-    with pytest.raises(pk.EesdError):
-        g.generate(prompt, 8)                      # no predictor installed
+    if first:
+        with pytest.raises(pk.EesdError):
+            g.generate(prompt, 8)                      # no predictor installed
     g.set_calibration(cw_gpu, 0.2, 0.5, 0.5)
-    cali = orc.CaliTS(0.2, 0.5, 0.5, seed=4)
+    cali = orc.CaliTS(0.2, 0.5, 0.5, seed=seed)
     n_new = 40
     trace = []
     want = o.generate_cali(prompt, n_new, cw_np, cali, trace=trace)
@@ -82,14 +83,30 @@ def test_cali_generation_matches_oracle(name):
     safe_len = next((i for i in range(n_new) if top2_gap(logits[i]) <= 2 * tol), n_new)
     assert got[:safe_len] == want[:safe_len]
     # the K sequence is the oracle's as long as no decision sat inside the score tolerance
-    margins = [abs(theta - orc.uniform(4, orc.STREAM_TS_CHI, r + 1, k + 1)) for r, rec in enumerate(trace)
+    margins = [abs(theta - orc.uniform(seed, orc.STREAM_TS_CHI, r + 1, k + 1)) for r, rec in enumerate(trace)
                for k, (_, theta, _) in enumerate(rec["scores"])]
-    if name == "tiny_fp32":      # for this model and seed the full comparison below does run
-        assert safe_len == n_new and min(margins) > 0.3 * tol + 1e-3
-    if safe_len == n_new and min(margins) > 0.3 * tol + 1e-3:
+    safe = safe_len == n_new and min(margins) > 0.3 * tol + 1e-3
+    if safe:
         assert (st.rounds, st.drafted, st.accepted) == (o.stats.rounds, o.stats.drafted, o.stats.accepted)
         assert g.cali_state() == (cali.theta_hat, cali.weight, cali.n)
     assert len({rec["K"] for rec in trace}) > 1
+    return safe
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_cali_generation_matches_oracle(name):
+    """Whole generations under the calibrated controller.  Rounds, drafts, acceptances and the posterior can only be
+    compared for a run none of whose decisions sits inside the tolerance of the scores and none of whose greedy tokens
+    is a near-tie; whether that holds is decided from the ORACLE's margins.  For the fp32 model such a run exists and
+    the comparison is unconditional.  For the bf16 model it cannot be: with random weights every greedy stream meets
+    a top-2 gap below twice the bf16 tolerance within a few tokens (a CPU search over 5 weight seeds x 3 prompts found
+    no stream that gets past 6), so there the text is compared up to the first near-tie and the controller's
+    decisions are covered unconditionally by the teacher-forced test above (scores within tolerance and an identical
+    posterior after every round, both weight layouts)."""
+    require_gpu()
+    safe = _cali_generation_case(name, 4, True)
+    if name == "tiny_fp32":
+        assert safe
 
 
 def test_cali_with_tree_and_argument_checks():
