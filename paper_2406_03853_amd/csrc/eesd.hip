@@ -45,6 +45,7 @@ static int g_nw_epi[4] = {0, 0, 0, 0};   // waves per workgroup of the per-tile 
 static int g_pf_kc = 0;        // 256: prefill blocks take 256-column chunks (default 128)
 static int g_pf_rows = 0;      // rows of a prefill block on tile-major weights: 128 (gemm_tile_kernel), 256 or 512 (gemm_pf_kernel; 0 = 512), read by eesd_create
 static int g_pf_ts = 0;        // gemm_pf_kernel: tile slots per workgroup for one-tile-per-group matrices (4 or 7; 0 = by tile count)
+static int g_grp_minsteps = -1; // row-group kernel, residual products: 4 waves instead of 8 while a wave would get fewer 128-column steps than this (-1: built-in)
 static int g_pf_nbw = 0;       // gemm_pf_kernel: 16-token blocks per wave (1, 2, 4; 0 = by rows and grid size)
 static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: by rows and tile count
 static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
@@ -53,7 +54,7 @@ extern "C" int eesd_set_tunable(const char* name, int value) {
     if (!name) return EESD_EINVAL;
     struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
                                              {"mfma_ksplit", &g_mfma_ksplit}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
-                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"pf_rows", &g_pf_rows}, {"pf_ts", &g_pf_ts}, {"pf_nbw", &g_pf_nbw}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
+                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"pf_rows", &g_pf_rows}, {"pf_ts", &g_pf_ts}, {"grp_minsteps", &g_grp_minsteps}, {"pf_nbw", &g_pf_nbw}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
     for (auto& e : t)
         if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
     return EESD_EINVAL;
@@ -295,8 +296,11 @@ static hipError_t launch_group(const GemmP& p, hipStream_t st) {
     if (EPI == EPI_RESID && p.y_partial) return hipErrorInvalidValue;
     const int units = p.out_rows / 4, max_units = (units + p.n_groups - 1) / p.n_groups;
     const int tmax = (max_units * 4 + 15) / 16;
-    int nw = 8;
+    int nw = g_nw_epi[EPI] ? std::min(g_nw_epi[EPI], 8) : 8;
     const int steps = p.in_dim / 128;
+    // residual products of blocks of 2 rows or more whose waves would get fewer than 14 steps each (13B shape: both; 70B shape: the
+    // attention output): 4 waves (measured -1.1 us per 13B-shape layer, -0.3 us per 70B-shape layer; single rows +0.4 us)
+    if (EPI == EPI_RESID && !g_nw_epi[EPI] && steps / 8 < (g_grp_minsteps < 0 ? (p.M >= 2 ? 14 : 0) : g_grp_minsteps)) nw = 4;
     while (nw > 1 && steps / nw < 2) nw >>= 1;
     const size_t lds = (size_t)nw * tmax * 1024;
     GemmP pl = p;
