@@ -187,6 +187,7 @@ static KVView kv_view(const eesd_ctx* c, int cache) {
     v.n_kv_heads = c->cfg.n_kv_heads;
     v.head_dim = c->cfg.head_dim;
     v.v_transposed = is_bf16(c) ? 1 : 0;
+    v.tiled = (is_bf16(c) && c->page_tokens % 32 == 0) ? 1 : 0;     // operand order: what the MFMA attention reads with contiguous lanes
     return v;
 }
 
@@ -1660,7 +1661,7 @@ __global__ void kv_gather_kernel(KVView kv, bool is_v, int n_tokens, float* __re
     int row = kv.n_kv_heads * kv.head_dim;
     if (idx >= n_tokens * row) return;
     int t = idx / row, r = idx - t * row, h = r / kv.head_dim, c = r - h * kv.head_dim;
-    long long off = is_v ? kv_v_elem(kv, h, t, c) : kv_k_row(kv, h, t) + c;
+    long long off = is_v ? kv_v_elem(kv, h, t, c) : kv_k_elem(kv, h, t, c);
     out[idx] = load_as_f32<KT>((const KT*)kv.pool + off);
 }
 
@@ -1674,7 +1675,7 @@ __global__ void kv_pattern_kernel(KVView kv, int n_tokens, unsigned salt) {
     x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
     float kval = ((float)(x & 0xffff) / 65536.0f - 0.5f) * 2.0f;
     float vval = ((float)(x >> 16) / 65536.0f - 0.5f) * 2.0f;
-    store_from_f32<KT>((KT*)kv.pool + kv_k_row(kv, h, t) + c, kval);
+    store_from_f32<KT>((KT*)kv.pool + kv_k_elem(kv, h, t, c), kval);
     store_from_f32<KT>((KT*)kv.pool + kv_v_elem(kv, h, t, c), vval);
 }
 
