@@ -66,7 +66,8 @@ typedef struct eesd_config {
     int32_t dtype;           /* EESD_DTYPE_*: storage type of the weights and of the KV cache;
                                 accumulation, residual stream, logits and probabilities are fp32 */
     int32_t max_seq;         /* most tokens the KV cache can hold */
-    int32_t kv_page;         /* tokens per KV page (power of two, >= 16) */
+    int32_t kv_page;         /* tokens per KV page (power of two, >= 16); bf16 caches with pages of 32 tokens or more are kept in
+                                the order of the attention's MFMA operands (contiguous reads), smaller pages row by row */
     int32_t k_cap;           /* most draft tokens per round, 1..15 */
     float temperature;       /* 0 => greedy (Section 4.1 footnote); > 0 => sampling at that temperature */
     uint64_t seed;           /* seed of the counter-based uniforms (draft, accept, resample, controller) */

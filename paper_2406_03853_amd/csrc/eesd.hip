@@ -778,14 +778,32 @@ static int launch_embed(eesd_ctx* c, const int32_t* tok_dev, int M) {
     return EESD_OK;
 }
 
+// x = embedding rows of the tokens and, for the MFMA family, xb = RMSNorm(x; first layer's gain): one kernel on bf16
+// models (the sum of squares runs in the order of rmsnorm_bf16_kernel's waves - 16 wave sums added in order - so
+// the result is that kernel's up to the order of additions inside a wave)
+static int launch_embed_norm(eesd_ctx* c, const int32_t* tok_dev, int M, bool mfma) {
+    const int d = c->cfg.d_model;
+    if (mfma && is_bf16(c) && d % 8 == 0 && d <= RN_MAX_PIECES * 8 * EN_THREADS) {
+        bf16_t* xp = (M > MAX_ROWS && c->pf_wide) ? c->xpb : nullptr;
+        c->xb_has_ssq = false;
+        hipLaunchKernelGGL(embed_norm_kernel, dim3(M), dim3(EN_THREADS), 0, c->stream, (const bf16_t*)c->w.tok_emb, tok_dev, c->x, d,
+                           (const bf16_t*)c->layers[0].attn_norm, c->cfg.rms_eps, d, c->xb, d, xp);
+        HIP_TRY(c, hipGetLastError());
+        return EESD_OK;
+    }
+    int rc = launch_embed(c, tok_dev, M);
+    if (rc) return rc;
+    if (mfma && (rc = launch_rmsnorm_bf16(c, c->x, M, c->layers[0].attn_norm, c->xb, d))) return rc;
+    return EESD_OK;
+}
+
 // Target forward over M rows whose tokens are tok_dev[0..M) at positions pos0.. :
 // all L layers (plus the early-exit layer's K/V after layer N); leaves hidden states in c->x
 // and, in the MFMA family, RMSNorm(x; final_norm) in c->xb.
 static int run_target_rows(eesd_ctx* c, const int32_t* tok_dev, int M, int pos0, bool mfma) {
     const eesd_config& g = c->cfg;
-    int rc = launch_embed(c, tok_dev, M);
+    int rc = launch_embed_norm(c, tok_dev, M, mfma);
     if (rc) return rc;
-    if (mfma && (rc = launch_rmsnorm_bf16(c, c->x, M, c->layers[0].attn_norm, c->xb, g.d_model))) return rc;
     for (int l = 0; l < g.n_layers; ++l) {
         const bool ee_next = (l + 1 == g.n_draft_layers);
         const void* next_gain = ee_next ? c->w.ee_layer.attn_norm : (l + 1 < g.n_layers ? c->layers[l + 1].attn_norm : c->w.final_norm);
@@ -807,9 +825,8 @@ static int run_target_rows_reusing(eesd_ctx* c, int K, int pos0) {
     const eesd_config& g = c->cfg;
     const int d = g.d_model, N = g.n_draft_layers, M = K + 1;
     const bool mfma1 = pick_mfma(c, 1), mfmaM = pick_mfma(c, M);
-    int rc = launch_embed(c, c->blk_tok + K, 1);
+    int rc = launch_embed_norm(c, c->blk_tok + K, 1, mfma1);
     if (rc) return rc;
-    if (mfma1 && (rc = launch_rmsnorm_bf16(c, c->x, 1, c->layers[0].attn_norm, c->xb, d))) return rc;
     for (int l = 0; l < N; ++l) {
         const void* next_gain = l + 1 < N ? c->layers[l + 1].attn_norm : c->w.ee_layer.attn_norm;
         if ((rc = run_layer(c, c->layers[l], l, 1, pos0 + K, mfma1, next_gain))) return rc;
@@ -1306,9 +1323,7 @@ extern "C" int eesd_draft_step(eesd_ctx* c, int32_t* tok_or_null) {
     int rc = ensure_pages(c, pos + 1);
     if (rc) return rc;
     const bool mfma = pick_mfma(c, 1);
-    rc = launch_embed(c, c->blk_tok + i, 1);
-    if (rc) return rc;
-    if (mfma && (rc = launch_rmsnorm_bf16(c, c->x, 1, c->layers[0].attn_norm, c->xb, g.d_model))) return rc;
+    if ((rc = launch_embed_norm(c, c->blk_tok + i, 1, mfma))) return rc;
     for (int l = 0; l < g.n_draft_layers; ++l) {
         const void* next_gain = l + 1 < g.n_draft_layers ? c->layers[l + 1].attn_norm : c->w.ee_layer.attn_norm;
         if ((rc = run_layer(c, c->layers[l], l, 1, pos, mfma, next_gain))) return rc;
