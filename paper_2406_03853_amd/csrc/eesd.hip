@@ -299,9 +299,9 @@ static hipError_t launch_group(const GemmP& p, hipStream_t st) {
     const int tmax = (max_units * 4 + 15) / 16;
     int nw = g_nw_epi[EPI] ? std::min(g_nw_epi[EPI], 8) : 8;
     const int steps = p.in_dim / 128;
-    // residual products of blocks of 2 rows or more whose waves would get fewer than 14 steps each (13B shape: both; 70B shape: the
-    // attention output): 4 waves (measured -1.1 us per 13B-shape layer, -0.3 us per 70B-shape layer; single rows +0.4 us)
-    if (EPI == EPI_RESID && !g_nw_epi[EPI] && steps / 8 < (g_grp_minsteps < 0 ? (p.M >= 2 ? 14 : 0) : g_grp_minsteps)) nw = 4;
+    // residual products whose waves would get fewer than 14 steps each (13B shape: both; 70B shape: the attention output): 4 waves
+    // (measured -1.1 us per 13B-shape layer, -0.3 us per 70B-shape layer)
+    if (EPI == EPI_RESID && !g_nw_epi[EPI] && steps / 8 < (g_grp_minsteps < 0 ? 14 : g_grp_minsteps)) nw = 4;
     while (nw > 1 && steps / nw < 2) nw >>= 1;
     const size_t lds = (size_t)nw * tmax * 1024;
     GemmP pl = p;
