@@ -226,6 +226,11 @@ double eesd_host_uniform(uint64_t seed, int32_t stream, int64_t round, int32_t s
 int eesd_host_draw_k(double alpha, double beta, uint64_t seed, int64_t round, int32_t k_max);
 /* Posterior update of Eq. 3-4 in place (reading as eesd_config.ts_update). */
 int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t n_drafted, int32_t reading);
+/* Where the operand-order layouts keep an element, as the kernels compute it (for tests of the layouts; -1 on bad
+ * arguments).  what = 0: key of slot a (position inside its KV page), channel b, head_dim n -> element offset inside one
+ * KV head's block of the page; 1: the same for a value; 2: activation row a, column b of a prefill block with 32 n
+ * columns -> element offset inside the block's buffer. */
+int64_t eesd_host_layout_offset(int32_t what, int32_t a, int32_t b, int32_t n);
 
 /* ---- Thompson sampling with calibration (Section 3.3 Eq. 5-8, Algorithm 3) ------------ */
 /* The predictor of Eq. 5 and the hyper-parameters of the Gaussian posterior.  w and wp are DEVICE

@@ -83,7 +83,7 @@ _LIB = None
 EXPORTS = ["eesd_create", "eesd_destroy", "eesd_prefill", "eesd_draft_step", "eesd_verify", "eesd_accept", "eesd_accepted_tokens", "eesd_rollback",
            "eesd_generate", "eesd_get_stats", "eesd_last_error", "eesd_set_draft_schedule", "eesd_next_draft_len",
            "eesd_debug_read", "eesd_debug_force_drafts", "eesd_debug_force_pending", "eesd_debug_rollback", "eesd_debug_fill_cache",
-           "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_set_calibration", "eesd_cali_score",
+           "eesd_host_uniform", "eesd_host_draw_k", "eesd_host_ts_update", "eesd_host_layout_offset", "eesd_set_calibration", "eesd_cali_score",
            "eesd_host_cali_decide", "eesd_host_cali_update", "eesd_debug_profile_begin", "eesd_debug_profile_end", "eesd_debug_copy", "eesd_set_tunable", "eesd_op_accept", "eesd_op_accept_logits", "eesd_op_softmax_sample", "eesd_op_gemm", "eesd_op_gemm_noalloc", "eesd_pack_weight"]
 
 
@@ -123,6 +123,8 @@ def lib() -> C.CDLL:
     L.eesd_debug_copy.argtypes = [VP, VP, C.c_size_t, VP]
     L.eesd_host_uniform.argtypes = [C.c_uint64, I32, C.c_int64, I32, I32]
     L.eesd_host_uniform.restype = C.c_double
+    L.eesd_host_layout_offset.argtypes = [I32, I32, I32, I32]
+    L.eesd_host_layout_offset.restype = C.c_int64
     L.eesd_host_draw_k.argtypes = [C.c_double, C.c_double, C.c_uint64, C.c_int64, I32]
     L.eesd_host_ts_update.argtypes = [P(C.c_double), P(C.c_double), I32, I32, I32]
     L.eesd_set_calibration.argtypes = [VP, P(_Calibration)]
@@ -137,7 +139,7 @@ def lib() -> C.CDLL:
     L.eesd_op_gemm_noalloc.argtypes = [VP, VP, VP, I32, I32, I32, I32, VP]
     L.eesd_pack_weight.argtypes = [VP, VP, I32, I32, I32, I32, VP]
     for name in EXPORTS:
-        if name not in ("eesd_destroy", "eesd_last_error", "eesd_host_uniform"):
+        if name not in ("eesd_destroy", "eesd_last_error", "eesd_host_uniform", "eesd_host_layout_offset"):
             getattr(L, name).restype = C.c_int
     _LIB = L
     return L
@@ -153,6 +155,10 @@ def _ptr(arr: np.ndarray, ct):
 
 def host_uniform(seed: int, stream: int, rnd: int, slot: int = 0, sub: int = 0) -> float:
     return lib().eesd_host_uniform(seed, stream, rnd, slot, sub)
+
+
+def host_layout_offset(what: int, a: int, b: int, n: int) -> int:
+    return lib().eesd_host_layout_offset(what, a, b, n)
 
 
 def host_draw_k(alpha: float, beta: float, seed: int, rnd: int, k_max: int) -> int:

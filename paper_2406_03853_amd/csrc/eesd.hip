@@ -982,6 +982,14 @@ extern "C" int eesd_host_draw_k(double alpha, double beta, uint64_t seed, int64_
     if (!(alpha > 0.0) || !(beta > 0.0)) return EESD_EINVAL;
     return beta_ts_draw_k(alpha, beta, seed, round, k_max);
 }
+// The element offsets of the two operand-order layouts, as the kernels compute them.
+extern "C" int64_t eesd_host_layout_offset(int32_t what, int32_t a, int32_t b, int32_t n) {
+    if (a < 0 || b < 0 || n < 1) return -1;
+    if (what == 0) return n % 32 ? -1 : (int64_t)kv_tiled_k(a, b, n);       // key slot a (inside its page), channel b, head_dim n
+    if (what == 1) return n % 32 ? -1 : (int64_t)kv_tiled_v(a, b, n);       // value slot a, channel b, head_dim n
+    if (what == 2) return (int64_t)act_packed_offset(a, b, n);               // activation row a, column b, n = columns / 32
+    return -1;
+}
 extern "C" int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t n_drafted, int32_t reading) {
     if (!alpha || !beta || n_accepted < 0 || n_accepted > n_drafted || reading < 0 || reading > 1) return EESD_EINVAL;
     beta_ts_update(alpha, beta, n_accepted, n_drafted, reading);

@@ -79,3 +79,32 @@ def test_calibrated_controller_update_matches_both_readings():
             assert (th, w, n) == (c.theta_hat, c.weight, c.n)
     with pytest.raises(pk.EesdError):
         pk.host_cali_update(0.5, 1.0, 0, 3, 2, 0)
+
+
+def test_operand_order_layouts_are_permutations_with_the_mfma_lane_order():
+    """The operand-order layouts of the KV cache and of a prefill block's activation rows: every element has its own
+    place (a permutation of the block), and the places are those of the MFMA operands - lane l = 16 g + i of a 1 KB
+    block owns 16 contiguous bytes at 16 l."""
+    import paper_2406_03853_amd as pk
+    for hd in (64, 128):
+        page = 64
+        ks = np.array([[pk.host_layout_offset(0, s, c, hd) for c in range(hd)] for s in range(page)])
+        vs = np.array([[pk.host_layout_offset(1, s, c, hd) for c in range(hd)] for s in range(page)])
+        for off in (ks, vs):
+            assert sorted(off.ravel().tolist()) == list(range(page * hd))
+        for step in range(page // 32):
+            for r in range(32):
+                s = step * 32 + r
+                tile, i = (r >> 2) & 1, ((r >> 3) << 2) | (r & 3)          # tile A: slots 8a+b, tile B: 8a+4+b; row 4a+b
+                for c in range(hd):
+                    q, g, e = c // 32, (c % 32) // 8, c % 8
+                    assert ks[s, c] == ((((step * 2 + tile) * (hd // 32) + q) * 64) + 16 * g + i) * 8 + e
+                    dt, ci = c // 16, c % 16
+                    assert vs[s, c] == (((step * (hd // 16) + dt) * 64) + 16 * ((r >> 3) & 3) + ci) * 8 + (s & 7)
+    steps = 5
+    act = np.array([[pk.host_layout_offset(2, m, c, steps) for c in range(32 * steps)] for m in range(48)])
+    assert sorted(act.ravel().tolist()) == list(range(48 * 32 * steps))
+    for m in range(48):
+        for c in range(32 * steps):
+            assert act[m, c] == ((((m // 16) * steps + c // 32) * 64) + ((c % 32) // 8) * 16 + m % 16) * 8 + c % 8
+    assert pk.host_layout_offset(0, 0, 0, 48) == -1 and pk.host_layout_offset(7, 0, 0, 64) == -1
