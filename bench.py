@@ -111,7 +111,7 @@ def cpu_baseline(w, shape, temperature, mean_k, mean_commit, si):
     return out
 
 
-def latency_sweep(ctx, torch, cache_tokens, ks, shape, si):
+def latency_sweep(ctx, torch, cache_tokens, ks, shape, si, pk=None):
     """Draft-step, verify-pass and accept latency for fixed K over a cache of `cache_tokens` positions
     (filled with a deterministic pattern: attention cost depends on the shape only)."""
     res = {}
@@ -140,7 +140,29 @@ def latency_sweep(ctx, torch, cache_tokens, ks, shape, si):
         res[str(K + 1)] = {"verify_rows": K + 1, "verify_ms": tv / reps, "verify_GBps": b_verify / (tv / reps * 1e-3) / 1e9,
                            "verify_frac_of_peak": b_verify / (tv / reps * 1e-3) / 1e9 / HBM_PEAK_GBS,
                            "accept_us": ta / reps * 1e3, "draft_step_ms": (td / reps / K) if K else None}
+        if pk is not None:
+            res[str(K + 1)]["accept_all_rows_us"] = accept_walk_us(pk, torch, K, shape["vocab"])
     return res
+
+
+def accept_walk_us(pk, torch, K, vocab, reps=5):
+    """The verification tail when every draft is accepted (all K + 1 rows are walked; `accept_us` above is the run's own
+    decision, which with random weights stops at the first row): the library's accept on synthetic bf16 logit rows whose
+    draft distribution equals the target's, so that u q < p holds for every draft.  Host-timed, includes the call's
+    synchronisation."""
+    g = torch.Generator(device="cpu").manual_seed(K)
+    logits = (torch.randn(K + 1, vocab, generator=g) * 2.0).to(torch.bfloat16).cuda()
+    q_rows = torch.softmax(logits[:max(K, 1)].float(), dim=-1).contiguous()
+    p_rows = torch.empty(K + 1, vocab, device="cuda")
+    drafts = torch.randint(0, vocab, (K,), generator=g).to(torch.int32).cuda()
+    u = [0.5] * (K + 1)
+    a, _ = pk.op_accept_logits(logits, p_rows, q_rows, drafts, u, 1.0)
+    assert a == K, "synthetic rows were meant to accept every draft"
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        pk.op_accept_logits(logits, p_rows, q_rows, drafts, u, 1.0)
+    return (time.perf_counter() - t0) / reps * 1e6
 
 
 def summarise(stats, shape, n_prompt, max_new, bf16, si):
@@ -370,7 +392,7 @@ def main():
         # the verify micro-benchmark of the 70B shape: one block of 1, 2, 4, 8, 16 rows over a 2048-token cache, then the
         # accept / resample kernel on 32000-way bf16 logits with the context's seeded uniforms
         c4 = pk.EESD(w, max_seq=2048 + 64, temperature=1.0, seed=0, k_cap=15, kv_page=64, weight_layout=layout, logits_bf16=1)
-        out["latency_vs_K"] = {"cache_tokens": 2048, "logits": "bf16", "by_verify_rows": latency_sweep(c4, torch, 2048, (0, 1, 3, 7, 15), shape, si)}
+        out["latency_vs_K"] = {"cache_tokens": 2048, "logits": "bf16", "by_verify_rows": latency_sweep(c4, torch, 2048, (0, 1, 3, 7, 15), shape, si, pk)}
         c4.close()
         del c4
     if not args.no_cpu_baseline:
