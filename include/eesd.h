@@ -321,7 +321,8 @@ int eesd_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
  * "valu_nw", "valu_tpw", "valu_rp", "mfma_nw", "mfma_ksplit", "fuse_norm", "mfma_tile", "tile_kc", "tile_nwt", "pf_kc",
  * "pf_rows" (rows of a prefill block on tile-major weights, 128 / 256 / 512; read by eesd_create), "grp_minsteps" (row-group residual products take 4 waves below this many steps per wave), "pf_ts", "pf_nbw" (tile slots per
  * workgroup and 16-token blocks per wave of the prefill GEMM), "attn_split", "mfma_min_m", "nw_plain", "nw_resid", "nw_swiglu", "nw_qkv" (waves per workgroup of the per-tile
- * product by epilogue). */
+ * product by epilogue), "smp_spread" (the sampling tails of the draft step and of the accept at temperature > 0: 1 = three
+ * kernels over 64 workgroups per row, 0 = one workgroup, -1 = built-in: spread for vocabularies of 4096 to 65536 entries). */
 int eesd_set_tunable(const char* name, int value);
 
 /* ---- stand-alone kernels (device buffers in, host results out) ----------------------- */
@@ -331,8 +332,8 @@ int eesd_set_tunable(const char* name, int value);
 int eesd_op_accept(const float* p_rows, const float* q_rows, const int32_t* drafts, const double* uniforms,
                    int32_t K, int32_t vocab, int32_t greedy, void* hip_stream, int32_t* result);
 /* The verification tail as eesd_accept runs it, on given logit rows: p_logits DEVICE [K+1][vocab], fp32 or (logits_bf16 = 1)
- * bf16; row i becomes softmax(p_logits[i] / temperature) in p_rows[i] (DEVICE fp32 [K+1][vocab], rows 0..a only: the walk
- * stops at the first rejection), draft i is accepted iff u_i q_i(d_i) < p_i(d_i), the first rejected position is resampled
+ * bf16; row i becomes softmax(p_logits[i] / temperature) in p_rows[i] (DEVICE fp32 [K+1][vocab]; rows 0..a are always written, rows
+ * past the first rejection only by the kernels that handle all rows at once, see "smp_spread"), draft i is accepted iff u_i q_i(d_i) < p_i(d_i), the first rejected position is resampled
  * from norm(max(0, p - q)), K acceptances draw the bonus token from row K.  temperature 0: greedy on the logits, p_rows,
  * q_rows and uniforms unused.  q_rows, drafts, uniforms, result as eesd_op_accept. */
 int eesd_op_accept_logits(const void* p_logits, int32_t logits_bf16, float* p_rows, const float* q_rows, const int32_t* drafts,

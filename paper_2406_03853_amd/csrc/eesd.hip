@@ -46,6 +46,7 @@ static int g_pf_kc = 0;        // 256: prefill blocks take 256-column chunks (de
 static int g_pf_rows = 0;      // rows of a prefill block on tile-major weights: 128 (gemm_tile_kernel), 256 or 512 (gemm_pf_kernel; 0 = 512), read by eesd_create
 static int g_pf_ts = 0;        // gemm_pf_kernel: tile slots per workgroup for one-tile-per-group matrices (4 or 7; 0 = by tile count)
 static int g_grp_minsteps = -1; // row-group kernel, residual products: 4 waves instead of 8 while a wave would get fewer 128-column steps than this (-1: built-in)
+static int g_smp_spread = -1;      // draft-step sampling spread over 64 workgroups (three small kernels): 1 on, 0 off, -1 built-in (vocabularies of 4096 entries and more)
 static int g_pf_nbw = 0;       // gemm_pf_kernel: 16-token blocks per wave (1, 2, 4; 0 = by rows and grid size)
 static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: by rows and tile count
 static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
@@ -54,7 +55,7 @@ extern "C" int eesd_set_tunable(const char* name, int value) {
     if (!name) return EESD_EINVAL;
     struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
                                              {"mfma_ksplit", &g_mfma_ksplit}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
-                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"pf_rows", &g_pf_rows}, {"pf_ts", &g_pf_ts}, {"grp_minsteps", &g_grp_minsteps}, {"pf_nbw", &g_pf_nbw}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
+                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"pf_rows", &g_pf_rows}, {"pf_ts", &g_pf_ts}, {"smp_spread", &g_smp_spread}, {"grp_minsteps", &g_grp_minsteps}, {"pf_nbw", &g_pf_nbw}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
     for (auto& e : t)
         if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
     return EESD_EINVAL;
@@ -143,6 +144,7 @@ struct eesd_ctx {
     int ssq_slots;         // partial sums of squares a residual product leaves per row
     int row_cap;           // rows the activation buffers hold (16, PREFILL_ROWS, or up to PREFILL_ROWS_WIDE with pf_wide)
     int part_rows;         // rows of one slab of the K-split partial sums
+    char* spl_buf;      // chunk statistics of the sampling tails spread over workgroups (SPL_SCRATCH_BYTES)
     bf16_t *xpb, *abp, *actp;   // pf_wide: what xb, ab and actb hold for a prefill block, in operand order (written by the producers)
     bool pf_wide;          // prefill blocks go through gemm_pf_kernel (tile-major weights, every reduction a multiple of 256)
     hipEvent_t ev[4];
@@ -1033,7 +1035,7 @@ extern "C" void eesd_destroy(eesd_ctx* c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void* dev[] = {c->kv_pool, c->d_table, c->x, c->q, c->attn, c->act, c->logits, c->p_rows, c->q_logits, c->q_rows, c->part_o,
-                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->xpb, c->abp, c->actp, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb, c->hn_rows};
+                   c->part_ml, c->rope_cs, c->part, c->ssq, c->xb, c->xpb, c->abp, c->actp, c->spl_buf, c->ab, c->actb, c->blk_tok, c->prompt_dev, c->result_dev, c->tree_blk, c->h_t, c->cali_u, c->theta_dev, c->h_tb, c->hn_rows};
     for (void* p : dev)
         if (p) hipFree(p);
     if (c->h_table) hipHostFree(c->h_table);
@@ -1098,6 +1100,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     c->x = c->q = c->attn = c->act = c->logits = c->p_rows = c->q_logits = c->q_rows = c->part_o = c->part_ml = c->rope_cs = c->part = c->ssq = nullptr;
     c->xb_has_ssq = false;
     c->xb = c->ab = c->actb = c->xpb = c->abp = c->actp = nullptr;
+    c->spl_buf = nullptr;
     c->blk_tok = c->prompt_dev = c->result_dev = c->tree_blk = nullptr;
     c->h_t = c->cali_u = c->theta_dev = nullptr; c->h_tb = nullptr; c->hn_rows = nullptr;
     c->cali_set = false; memset(&c->cali, 0, sizeof c->cali);
@@ -1181,6 +1184,7 @@ extern "C" int eesd_create(const eesd_config* cfg, const eesd_weights* w, void* 
     if ((rc = dev_alloc(c, &c->xb, R * d))) return bail(rc);
     if ((rc = dev_alloc(c, &c->ab, R * qd))) return bail(rc);
     if ((rc = dev_alloc(c, &c->actb, R * f))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->spl_buf, (size_t)SPL_SCRATCH_BYTES))) return bail(rc);
     if ((rc = dev_alloc(c, &c->blk_tok, (size_t)MAX_ROWS + 1))) return bail(rc);
     if ((rc = dev_alloc(c, &c->prompt_dev, (size_t)g.max_seq))) return bail(rc);
     if ((rc = dev_alloc(c, &c->result_dev, (size_t)2 + MAX_ROWS))) return bail(rc);
@@ -1254,8 +1258,35 @@ static int tree_width(const eesd_ctx* c) { return c->cfg.tree_width >= 2 ? c->cf
 static int rows_cap(const eesd_ctx* c) { return 1 + c->cfg.k_cap * tree_width(c); }
 
 // softmax(row / T) -> probs, draw with u (greedy: argmax); the row is fp32 or bf16 logits
+// whether a draft step at temperature > 0 samples with the three kernels spread over the chip (sampling.hiph)
+static bool smp_spread(int V) { return V <= SPL_MAX_V && (g_smp_spread < 0 ? V >= 4096 : g_smp_spread != 0); }
+
+template <typename LT>
+static hipError_t launch_spread_sample(hipStream_t st, const LT* row, float* probs, int V, float inv_t, double u, int forced, SplScratch sc,
+                                       int32_t* tok_out) {
+    hipLaunchKernelGGL(softmax_part_kernel<LT>, dim3(SPL_CHUNKS), dim3(SPL_THREADS), 0, st, row, V, inv_t, sc);
+    hipLaunchKernelGGL(softmax_norm_kernel<LT>, dim3(SPL_CHUNKS), dim3(SPL_THREADS), 0, st, row, probs, V, inv_t, sc);
+    hipLaunchKernelGGL(sample_pick_kernel, dim3(1), dim3(64), 0, st, (const float*)probs, V, u, forced, sc, tok_out);
+    return hipGetLastError();
+}
+
+// the verify side of the same: all K + 1 rows at once
+template <typename LT>
+static hipError_t launch_spread_accept(hipStream_t st, const LT* p_logits, float* p_rows, const float* q_rows, const int32_t* drafts, int K, int V,
+                                       float inv_t, const AcceptU& uu, SplScratch sc, int32_t* result, int32_t* pending_out) {
+    hipLaunchKernelGGL(softmax_part_kernel<LT>, dim3(SPL_CHUNKS, K + 1), dim3(SPL_THREADS), 0, st, p_logits, V, inv_t, sc);
+    hipLaunchKernelGGL(accept_norm_kernel<LT>, dim3(SPL_CHUNKS, K + 1), dim3(SPL_THREADS), 0, st, p_logits, p_rows, q_rows, drafts, K, V, inv_t, uu, sc);
+    hipLaunchKernelGGL(accept_pick_kernel, dim3(1), dim3(64), 0, st, (const float*)p_rows, q_rows, K, V, uu.u[K], sc, result, pending_out);
+    return hipGetLastError();
+}
+
 static hipError_t launch_softmax_sample(eesd_ctx* c, const void* row, float* probs, double u, int forced, int32_t* tok_out) {
     const int V = c->cfg.vocab;
+    if (!greedy(c) && smp_spread(V)) {
+        const SplScratch sc = spl_scratch(c->spl_buf);
+        return lb16(c) ? launch_spread_sample(c->stream, (const bf16_t*)row, probs, V, inv_temperature(c), u, forced, sc, tok_out)
+                       : launch_spread_sample(c->stream, (const float*)row, probs, V, inv_temperature(c), u, forced, sc, tok_out);
+    }
     if (lb16(c)) {
         hipError_t e = smp_allow(softmax_sample_kernel<bf16_t>, V);
         if (e != hipSuccess) return e;
@@ -1453,7 +1484,13 @@ extern "C" int eesd_accept(eesd_ctx* c, const double* uniforms_or_null, int32_t*
     uu.u[K] = uniforms_or_null ? uniforms_or_null[K] : uniform53(g.seed, STREAM_RESAMPLE, c->round, 0, 0);
     for (int i = 0; i <= K; ++i)
         if (!(uu.u[i] >= 0.0 && uu.u[i] < 1.0)) return fail(c, EESD_EINVAL, "accept: uniform %d outside [0,1)", i);
-    if (lb16(c)) {
+    if (!greedy(c) && smp_spread(g.vocab)) {
+        const SplScratch sc = spl_scratch(c->spl_buf);
+        HIP_TRY(c, lb16(c) ? launch_spread_accept(c->stream, (const bf16_t*)c->logits, c->p_rows, c->q_rows, c->blk_tok + 1, K, g.vocab,
+                                                  inv_temperature(c), uu, sc, c->result_dev, c->blk_tok)
+                           : launch_spread_accept(c->stream, (const float*)c->logits, c->p_rows, c->q_rows, c->blk_tok + 1, K, g.vocab,
+                                                  inv_temperature(c), uu, sc, c->result_dev, c->blk_tok));
+    } else if (lb16(c)) {
         HIP_TRY(c, smp_allow(accept_kernel<bf16_t>, g.vocab));
         hipLaunchKernelGGL(accept_kernel<bf16_t>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(g.vocab), c->stream, (const bf16_t*)c->logits, c->p_rows, c->q_rows,
                            c->blk_tok + 1, K, g.vocab, inv_temperature(c), greedy(c), 1, uu, c->result_dev, c->blk_tok, smp_use_lds(g.vocab));
@@ -1896,10 +1933,14 @@ extern "C" int eesd_op_accept_logits(const void* p_logits, int32_t logits_bf16, 
         }
     hipStream_t st = (hipStream_t)hip_stream;
     int32_t* d_res = nullptr;
-    if (hipMalloc((void**)&d_res, 2 * sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
+    if (hipMalloc((void**)&d_res, 256 + SPL_SCRATCH_BYTES) != hipSuccess) return EESD_ENOMEM;      // the result, then the spread kernels' chunk statistics
     const float inv_t = greedy_flag ? 1.0f : 1.0f / temperature;
     hipError_t e;
-    if (logits_bf16) {
+    if (!greedy_flag && smp_spread(vocab)) {
+        const SplScratch sc = spl_scratch((char*)d_res + 256);
+        e = logits_bf16 ? launch_spread_accept(st, (const bf16_t*)p_logits, p_rows, q_rows, drafts, K, vocab, inv_t, uu, sc, d_res, (int32_t*)nullptr)
+                        : launch_spread_accept(st, (const float*)p_logits, p_rows, q_rows, drafts, K, vocab, inv_t, uu, sc, d_res, (int32_t*)nullptr);
+    } else if (logits_bf16) {
         e = smp_allow(accept_kernel<bf16_t>, vocab);
         if (e == hipSuccess)
             hipLaunchKernelGGL(accept_kernel<bf16_t>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(vocab), st, (const bf16_t*)p_logits, p_rows, q_rows, drafts, K, vocab,
@@ -1923,9 +1964,12 @@ extern "C" int eesd_op_softmax_sample(const float* logits, float* probs, int32_t
     if (temperature > 0.f && !probs) return EESD_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     int32_t* d_tok = nullptr;
-    if (hipMalloc((void**)&d_tok, sizeof(int32_t)) != hipSuccess) return EESD_ENOMEM;
+    if (hipMalloc((void**)&d_tok, 256 + SPL_SCRATCH_BYTES) != hipSuccess) return EESD_ENOMEM;      // the token, then the spread kernels' chunk statistics
     hipError_t e = smp_allow(softmax_sample_kernel<float>, vocab);
-    if (e == hipSuccess) {
+    if (e == hipSuccess && temperature > 0.f && smp_spread(vocab)) {
+        const SplScratch sc = spl_scratch((char*)d_tok + 256);
+        e = launch_spread_sample(st, logits, probs, vocab, 1.0f / temperature, u, -1, sc, d_tok);
+    } else if (e == hipSuccess) {
         hipLaunchKernelGGL(softmax_sample_kernel<float>, dim3(1), dim3(SMP_THREADS), smp_lds_bytes(vocab), st, logits, probs, vocab,
                            temperature > 0.f ? 1.0f / temperature : 1.0f, temperature == 0.f, u, -1, d_tok, smp_use_lds(vocab));
         e = hipGetLastError();

@@ -186,10 +186,44 @@ def test_gemm_mfma_launch_shapes(nw):
         pk.set_tunable("mfma_nw", 0)
 
 
-@pytest.mark.parametrize("V", [512, 1000, 32000, 50257])   # the last one is too long for the LDS-resident row
-def test_softmax_sample_bit_exact_tokens(V):
+@pytest.mark.parametrize("spread", [0, 1])                  # one workgroup / three kernels over 64 workgroups
+@pytest.mark.parametrize("V", [512, 1000, 32000, 50257, 65536])   # 50257 is too long for the LDS-resident row
+def test_softmax_sample_bit_exact_tokens(V, spread):
     require_gpu()
     pk = _pk()
+    pk.set_tunable("smp_spread", spread)
+    try:
+        _softmax_sample_case(pk, V)
+    finally:
+        pk.set_tunable("smp_spread", -1)
+
+
+def test_softmax_sample_edge_uniforms_and_one_hot_rows():
+    """Uniforms at both ends of [0, 1) and rows whose whole mass sits on one entry (first, last, in the ragged tail of
+    the last chunk), in both kernels: the token is the rule's on the GPU's own row."""
+    require_gpu()
+    pk = _pk()
+    V = 32000
+    try:
+        for spread in (0, 1):
+            pk.set_tunable("smp_spread", spread)
+            for hot in (0, 31, 16383, 31743, 31999):
+                row = np.full(V, -200.0, np.float32)
+                row[hot] = 5.0
+                for u in (0.0, 0.5, np.nextafter(1.0, 0.0)):
+                    probs = torch.zeros(V, device="cuda")
+                    tok = pk.op_softmax_sample(torch.from_numpy(row).cuda(), probs, 1.0, float(u))
+                    assert tok == hot == orc.decide_sample(probs.cpu().numpy(), float(u)), (spread, hot, u)
+            row = si.make_logit_rows(1, V, seed=5)[0]
+            for u in (0.0, np.nextafter(1.0, 0.0)):
+                probs = torch.zeros(V, device="cuda")
+                tok = pk.op_softmax_sample(torch.from_numpy(row).cuda(), probs, 1.0, float(u))
+                assert tok == orc.decide_sample(probs.cpu().numpy(), float(u)), (spread, u)
+    finally:
+        pk.set_tunable("smp_spread", -1)
+
+
+def _softmax_sample_case(pk, V):
     logits = si.make_logit_rows(24, V, seed=V)
     us = si.make_uniforms(24, seed=V + 1)
     for i in range(24):
@@ -256,16 +290,49 @@ def test_accept_special_rows():
     assert pk.op_accept(torch.from_numpy(lg).cuda(), None, d, None, greedy=True) == orc.decide_accept(lg, None, d.cpu().numpy(), None, None, True)
 
 
+@pytest.mark.parametrize("spread", [0, 1])       # one workgroup walking the rows / all rows at once over 64 workgroups each
 @pytest.mark.parametrize("K", [0, 1, 3, 7, 15])
 @pytest.mark.parametrize("bf16", [1, 0])
-def test_accept_on_logit_rows_bit_exact(K, bf16):
+def test_accept_on_logit_rows_bit_exact(K, bf16, spread):
+    require_gpu()
+    pk = _pk()
+    pk.set_tunable("smp_spread", spread)
+    try:
+        _accept_on_logit_rows_case(pk, K, bf16, 32000 if K != 3 else 50257, spread)
+    finally:
+        pk.set_tunable("smp_spread", -1)
+
+
+def test_accept_on_logit_rows_rejected_with_an_empty_residual():
+    """A draft whose entry has probability 0 under both models is rejected (u * 0 < 0 is false); with q equal to the
+    kernel's own p row entry by entry the residual max(0, p - q) sums to 0 and the next token is drawn from p itself."""
+    require_gpu()
+    pk = _pk()
+    V = 32000
+    try:
+        for spread in (0, 1):
+            pk.set_tunable("smp_spread", spread)
+            lg32 = si.make_logit_rows(2, V, seed=77)
+            lg32[0, 1234] = -300.0
+            lg = torch.from_numpy(lg32).cuda()
+            us = np.array([0.3, 0.61])
+            p_rows = torch.zeros((2, V), device="cuda")
+            dd = torch.tensor([1234], dtype=torch.int32, device="cuda")
+            pk.op_accept_logits(lg, p_rows, torch.zeros((1, V), device="cuda"), dd, us, 1.0)      # first call: the kernel's p rows
+            q = p_rows[:1].clone()
+            assert float(q[0, 1234]) == 0.0
+            a, y = pk.op_accept_logits(lg, p_rows, q, dd, us, 1.0)
+            p_gpu = p_rows.cpu().numpy()
+            assert (a, y) == (0, orc.decide_sample(p_gpu[0], us[1])) == orc.decide_accept(p_gpu, q.cpu().numpy(), [1234], us[:1], us[1], greedy=False)
+    finally:
+        pk.set_tunable("smp_spread", -1)
+
+
+def _accept_on_logit_rows_case(pk, K, bf16, V, spread):
     """The verification tail on 32000-way logit rows stored as bf16 (and as fp32): the bf16 values are the INPUT of
     both sides.  The probability rows the kernel leaves equal the fp64 softmax of those logits to fp32 rounding, and
     the decision is exactly the oracle's rule on the kernel's own rows with the same uniforms.  Greedy: argmax over
     exactly representable values, so the oracle's rule on the widened logits must agree with no row read back."""
-    require_gpu()
-    pk = _pk()
-    V = 32000
     rej = 0
     for s in range(6):
         lg32 = si.make_logit_rows(K + 1, V, seed=1000 * K + s)
@@ -286,8 +353,9 @@ def test_accept_on_logit_rows_bit_exact(K, bf16):
         dd = torch.from_numpy(drafts).cuda()
         a, y = pk.op_accept_logits(lg, p_rows, qd, dd, us, T)
         p_gpu = p_rows.cpu().numpy()
-        assert np.isfinite(p_gpu[: a + 1]).all()
-        assert np.max(np.abs(p_gpu[: a + 1] - p_ref[: a + 1])) < 2e-6 * np.max(p_ref)
+        n_rows = K + 1 if spread else a + 1              # the one-workgroup walk stops after row a
+        assert np.isfinite(p_gpu[:n_rows]).all()
+        assert np.max(np.abs(p_gpu[:n_rows] - p_ref[:n_rows])) < 2e-6 * np.max(p_ref)
         assert orc.decide_accept(p_gpu, q.astype(np.float32) if K else None, drafts, us[:K], us[K], greedy=False) == (a, y), (s, a, y)
         rej += a < K
         # greedy on the same logits

@@ -80,8 +80,17 @@ def test_teacher_forced_rounds_match_oracle(name, temp, reuse):
 
 
 @pytest.mark.parametrize("name", list(SHAPES))
-@pytest.mark.parametrize("temp", [0.0, 1.0])
+@pytest.mark.parametrize("temp", [0.0, 1.0, -1.0])     # -1: temperature 1 with the draft sampling spread over 64 workgroups
 def test_gpu_decisions_follow_the_rule_on_the_gpus_own_rows(name, temp):
+    import paper_2406_03853_amd as pk
+    pk.set_tunable("smp_spread", 1 if temp < 0 else -1)
+    try:
+        _decisions_on_own_rows(name, abs(temp))
+    finally:
+        pk.set_tunable("smp_spread", -1)
+
+
+def _decisions_on_own_rows(name, temp):
     """Every integer a round decides - each draft token, the number of accepted drafts, the next token -
     must be exactly what the decision rule gives on the probability (greedy: logit) rows the GPU itself
     produced, with the same uniforms: no margin, no skip.  The GPU runs free (its own draft tokens, its own
