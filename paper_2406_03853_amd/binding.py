@@ -234,7 +234,10 @@ class EESD:
             self._h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except TypeError:       # interpreter shutdown: the module's globals are already gone, the process frees the context
+            pass
 
     def _ck(self, rc: int):
         if rc:

@@ -25,6 +25,25 @@ def _row(i, j, width):
     return 1 + (i - 1) * width + j
 
 
+@pytest.mark.parametrize("width", [2, 4])
+def test_tree_top_candidates_on_long_rows_with_ties(width):
+    """A vocabulary of several entries per thread and logits stored as bf16, so that equal values are common: the
+    candidates are the largest entries of the GPU's own row, equal values by lowest index."""
+    require_gpu()
+    shape = dict(si.TINY_GQA_BF16, vocab=9024, name="tiny_gqa_bf16_v9024")
+    steps = min(4, 15 // width)                      # a verify block holds 1 + K width <= 16 rows
+    o, g = make_pair(shape, 6, 96, 0.0, k_cap=steps, tree_width=width, logits_bf16=1)
+    g.prefill(si.make_prompt(12, shape["vocab"], 3))
+    ties = 0
+    for i in range(steps):
+        g.draft_step()
+        lg = np.asarray(g.draft_logits(i), np.float64)
+        want = sorted(range(len(lg)), key=lambda t: (-lg[t], t))[:width]
+        assert g.tree_tokens(1 + (i + 1) * width)[1 + i * width:] == want == orc.top_candidates(lg, width)
+        ties += len(set(lg[want])) < width or np.sum(lg == lg[want[-1]]) > 1
+    assert ties > 0
+
+
 @pytest.mark.parametrize("name", list(SHAPES))
 @pytest.mark.parametrize("width", [2, 3])
 def test_teacher_forced_tree_rounds_match_oracle(name, width):
