@@ -326,7 +326,7 @@ static hipError_t launch_pf_t(const GemmP& p, int tg, int gx, hipStream_t st) {
     hipError_t e = allow_lds((const void*)fn, lds);
     if (e != hipSuccess) return e;
     const int gy = (p.M + PF_NW * 16 * NBW - 1) / (PF_NW * 16 * NBW);
-    hipLaunchKernelGGL(fn, dim3(gx, gy), dim3(64 * PF_NW), lds, st, p, tg);
+    hipLaunchKernelGGL(fn, dim3((gx + 7) / 8 * 8 * gy), dim3(64 * PF_NW), lds, st, p, tg, gx, gy);
     return hipGetLastError();
 }
 template <int EPI, int TS>
