@@ -239,6 +239,12 @@ def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperatu
     return passes
 
 
+def progress(msg):
+    """One line on stderr when a phase or a step has finished: the run prints its JSON line only at the end, and a
+    harness that watches the output would take minutes of silence for a hang."""
+    print(f"bench.py: {msg}", file=sys.stderr, flush=True)
+
+
 def stored_traffic(workload):
     """HBM bytes per launch of the dominant kernel from the committed hardware-counter summary
     (profiles/hbm_traffic.json, written from two rocprofv3 --pmc runs), or None."""
@@ -300,6 +306,7 @@ def main():
     w = si.make_weights(shape, seed=wseed, device="cuda", correlated_draft=args.draft_correlation)
     torch.cuda.synchronize()
     t_weights = time.perf_counter() - t0
+    progress(f"weights of the {shape['name']} drawn in {t_weights:.1f} s")
     cpu_w = None if args.no_cpu_baseline else oracle_sample_weights(w, shape, si)
     bf16 = shape["dtype"] == "bf16"
     tiled = bf16 and not args.row_major_weights
@@ -328,15 +335,17 @@ def main():
             pk.calibration_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for i in range(args.warmup):
         ctx.generate(prompts[-1], max_new)
+        progress(f"warm-up step {i + 1} of {args.warmup} done")
     torch.cuda.synchronize()
     # ---- the timed region: exactly `steps` whole generations, nothing else on the stream ----
     t0 = time.perf_counter()
     stats = []
     for i in range(args.steps):
-        _, st = ctx.generate(prompts[i], max_new)
+        _, st = ctx.generate(prompts[i], max_new)     # returns after the generation's last synchronisation
         stats.append(st)
+        progress(f"step {i + 1} of {args.steps} done")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     # ---- after it: one more generation with a HIP event pair around every launch of the dominant kernel
@@ -344,6 +353,7 @@ def main():
     ctx.profile_begin(1 if bf16 else 0, 2, shape["d_model"])
     ctx.generate(prompts[0], max_new)
     n_launch, ms_kernel = ctx.profile_end()
+    progress("dominant kernel timed")
 
     passes, mean_k, mean_commit = summarise(stats, shape, n_prompt, max_new, bf16, si)
     passes["weight_init_s"] = t_weights
@@ -389,14 +399,17 @@ def main():
     if extras:
         # greedy decoding on the same weights (random weights: a greedy draft almost never matches, K collapses to 1)
         out["passes_T0"] = side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, 0.0, tiled, 2)
+        progress("greedy generations done")
         # the verify micro-benchmark of the 70B shape: one block of 1, 2, 4, 8, 16 rows over a 2048-token cache, then the
         # accept / resample kernel on 32000-way bf16 logits with the context's seeded uniforms
         c4 = pk.EESD(w, max_seq=2048 + 64, temperature=1.0, seed=0, k_cap=15, kv_page=64, weight_layout=layout, logits_bf16=1)
         out["latency_vs_K"] = {"cache_tokens": 2048, "logits": "bf16", "by_verify_rows": latency_sweep(c4, torch, 2048, (0, 1, 3, 7, 15), shape, si, pk)}
         c4.close()
         del c4
+        progress("latency sweep done")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cpu_w, shape, args.temperature, mean_k, mean_commit, si)
+        progress("oracle timed on the host")
     if extras:
         # the 13B shape: the 70B weights go first
         del w
@@ -409,13 +422,16 @@ def main():
         p13["workload"] = f"full EESD generation, {shape13['name']} (L={shape13['n_layers']}, N={shape13['n_draft_layers']}), prompt {np13}, {new13} new tokens, K cap {cap13}, temperature 1"
         p13["pass_frac"] = {"draft": p13["draft_step_GBps"] / HBM_PEAK_GBS, "verify": p13["verify_GBps"] / HBM_PEAK_GBS}
         out["passes_13b"] = p13
+        progress("13B-shape generations done")
         out["passes_13b_T0"] = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 0.0, True, 2)
+        progress("13B-shape greedy generations done")
         # the long-context configuration of the same shape: a 3840-token prompt, the cache grows to 4096
         _, _, npl, newl, capl = WORKLOADS["13b-long"]
         pl = side_generation(pk, si, torch, w13, shape13, npl, newl, capl, 1.0, True, 2)
         pl["workload"] = f"full EESD generation, {shape13['name']}, prompt {npl}, {newl} new tokens, K cap {capl}, temperature 1"
         pl["pass_frac"] = {"draft": pl["draft_step_GBps"] / HBM_PEAK_GBS, "verify": pl["verify_GBps"] / HBM_PEAK_GBS}
         out["passes_13b_long"] = pl
+        progress("13B-shape long-context generations done")
     print(json.dumps(out))
 
 
