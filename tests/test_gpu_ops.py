@@ -303,6 +303,24 @@ def test_accept_on_logit_rows_bit_exact(K, bf16, spread):
         pk.set_tunable("smp_spread", -1)
 
 
+@pytest.mark.parametrize("V", [4095, 4096, 65536, 65537])
+def test_sampling_tails_at_the_vocabulary_limits_of_the_spread_kernels(V):
+    """With the built-in choice the spread kernels take vocabularies of 4096 .. 65536 entries and the one-workgroup
+    kernels the rest: the rule's token on the kernel's own rows on both sides of both limits, ragged last chunks
+    included (65536 fills all 64 chunks of 1024 exactly)."""
+    require_gpu()
+    pk = _pk()
+    _accept_on_logit_rows_case(pk, 2, 0, V, int(4096 <= V <= 65536), n_seeds=2)
+    logits = si.make_logit_rows(3, V, seed=V)
+    us = si.make_uniforms(3, seed=V + 1)
+    for i in range(3):
+        probs = torch.zeros(V, device="cuda")
+        tok = pk.op_softmax_sample(torch.from_numpy(logits[i]).cuda(), probs, 1.0, float(us[i]))
+        p_gpu = probs.cpu().numpy()
+        assert np.max(np.abs(p_gpu - orc.softmax(logits[i].astype(np.float64)))) < 2e-6 * p_gpu.max()
+        assert tok == orc.decide_sample(p_gpu, float(us[i]))
+
+
 def test_accept_on_logit_rows_rejected_with_an_empty_residual():
     """A draft whose entry has probability 0 under both models is rejected (u * 0 < 0 is false); with q equal to the
     kernel's own p row entry by entry the residual max(0, p - q) sums to 0 and the next token is drawn from p itself."""
@@ -328,13 +346,13 @@ def test_accept_on_logit_rows_rejected_with_an_empty_residual():
         pk.set_tunable("smp_spread", -1)
 
 
-def _accept_on_logit_rows_case(pk, K, bf16, V, spread):
+def _accept_on_logit_rows_case(pk, K, bf16, V, spread, n_seeds=6):
     """The verification tail on 32000-way logit rows stored as bf16 (and as fp32): the bf16 values are the INPUT of
     both sides.  The probability rows the kernel leaves equal the fp64 softmax of those logits to fp32 rounding, and
     the decision is exactly the oracle's rule on the kernel's own rows with the same uniforms.  Greedy: argmax over
     exactly representable values, so the oracle's rule on the widened logits must agree with no row read back."""
     rej = 0
-    for s in range(6):
+    for s in range(n_seeds):
         lg32 = si.make_logit_rows(K + 1, V, seed=1000 * K + s)
         lg = torch.from_numpy(lg32).cuda()
         if bf16:
