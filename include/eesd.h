@@ -320,7 +320,7 @@ int eesd_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
  * "fuse_norm", restores the built-in heuristic):
  * "valu_nw", "valu_tpw", "valu_rp", "mfma_nw", "mfma_ksplit", "fuse_norm", "mfma_tile", "tile_kc", "tile_nwt", "pf_kc",
  * "pf_rows" (rows of a prefill block on tile-major weights, 128 / 256 / 512; read by eesd_create), "grp_minsteps" (row-group residual products take 4 waves below this many steps per wave), "pf_ts", "pf_nbw" (tile slots per
- * workgroup and 16-token blocks per wave of the prefill GEMM), "attn_split", "mfma_min_m", "nw_plain", "nw_resid", "nw_swiglu", "nw_qkv" (waves per workgroup of the per-tile
+ * workgroup and 16-token blocks per wave of the prefill GEMM), "pf_merge" (0: the 4-row tails of 20-row groups take a tile slot each instead of sharing one), "attn_split", "mfma_min_m", "nw_plain", "nw_resid", "nw_swiglu", "nw_qkv" (waves per workgroup of the per-tile
  * product by epilogue), "smp_spread" (the sampling tails of the draft step and of the accept at temperature > 0: 1 = three
  * kernels over 64 workgroups per row, 0 = one workgroup, -1 = built-in: spread for vocabularies of 4096 to 65536 entries). */
 int eesd_set_tunable(const char* name, int value);

@@ -47,7 +47,8 @@ static int g_pf_rows = 0;      // rows of a prefill block on tile-major weights:
 static int g_pf_ts = 0;        // gemm_pf_kernel: tile slots per workgroup for one-tile-per-group matrices (4 or 7; 0 = by tile count)
 static int g_grp_minsteps = -1; // row-group kernel, residual products: 4 waves instead of 8 while a wave would get fewer 128-column steps than this (-1: built-in)
 static int g_smp_spread = -1;      // draft-step sampling spread over 64 workgroups (three small kernels): 1 on, 0 off, -1 built-in (vocabularies of 4096 entries and more)
-static int g_pf_nbw = 0;       // gemm_pf_kernel: 16-token blocks per wave (1, 2, 4; 0 = by rows and grid size)
+static int g_pf_nbw = 0;
+static int g_pf_merge = -1;        // prefill GEMM: tails of 20-row groups gathered in one tile slot (0 off; -1 built-in: on)       // gemm_pf_kernel: 16-token blocks per wave (1, 2, 4; 0 = by rows and grid size)
 static int g_mfma_tile = 0;    // 1: every block of <= 16 rows takes the LDS-shared tile kernel; 2: none does; 0: by rows and tile count
 static int g_mfma_min_m = 1;   // AUTO: smallest M that takes the MFMA family on bf16 weights (measured: faster than the VALU family already at M = 1)
 
@@ -55,7 +56,7 @@ extern "C" int eesd_set_tunable(const char* name, int value) {
     if (!name) return EESD_EINVAL;
     struct { const char* n; int* p; } t[] = {{"valu_nw", &g_valu_nw}, {"valu_tpw", &g_valu_tpw}, {"valu_rp", &g_valu_rp},
                                              {"mfma_ksplit", &g_mfma_ksplit}, {"mfma_nw", &g_mfma_nw}, {"attn_split", &g_attn_split},
-                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"pf_rows", &g_pf_rows}, {"pf_ts", &g_pf_ts}, {"smp_spread", &g_smp_spread}, {"grp_minsteps", &g_grp_minsteps}, {"pf_nbw", &g_pf_nbw}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
+                                             {"mfma_min_m", &g_mfma_min_m}, {"mfma_tile", &g_mfma_tile}, {"pf_kc", &g_pf_kc}, {"pf_rows", &g_pf_rows}, {"pf_ts", &g_pf_ts}, {"pf_merge", &g_pf_merge}, {"smp_spread", &g_smp_spread}, {"grp_minsteps", &g_grp_minsteps}, {"pf_nbw", &g_pf_nbw}, {"nw_plain", &g_nw_epi[0]}, {"nw_resid", &g_nw_epi[1]}, {"nw_swiglu", &g_nw_epi[2]}, {"nw_qkv", &g_nw_epi[3]}, {"fuse_norm", &g_fuse_norm}, {"tile_kc", &g_tile_kc}, {"tile_nwt", &g_tile_nwt}};
     for (auto& e : t)
         if (!strcmp(e.n, name)) { *e.p = value; return EESD_OK; }
     return EESD_EINVAL;
@@ -320,21 +321,21 @@ static hipError_t launch_group(const GemmP& p, hipStream_t st) {
 
 // prefill blocks on tile-major weights: 8 waves x 16 NBW tokens against TS tile slots per workgroup
 template <int EPI, int TS, int NBW>
-static hipError_t launch_pf_t(const GemmP& p, int tg, int gx, hipStream_t st) {
+static hipError_t launch_pf_t(const GemmP& p, int tg, int gx, int merged, hipStream_t st) {
     const size_t lds = (size_t)2 * PF_QC * TS * 1024;
     auto fn = gemm_pf_kernel<EPI, TS, NBW>;
     hipError_t e = allow_lds((const void*)fn, lds);
     if (e != hipSuccess) return e;
     const int gy = (p.M + PF_NW * 16 * NBW - 1) / (PF_NW * 16 * NBW);
-    hipLaunchKernelGGL(fn, dim3((gx + 7) / 8 * 8 * gy), dim3(64 * PF_NW), lds, st, p, tg, gx, gy);
+    hipLaunchKernelGGL(fn, dim3((gx + 7) / 8 * 8 * gy), dim3(64 * PF_NW), lds, st, p, tg, gx, gy, merged);
     return hipGetLastError();
 }
 template <int EPI, int TS>
-static hipError_t launch_pf_ts(const GemmP& p, int tg, int gx, int nbw, hipStream_t st) {
-    if (nbw == 1) return launch_pf_t<EPI, TS, 1>(p, tg, gx, st);
-    if (nbw == 2) return launch_pf_t<EPI, TS, 2>(p, tg, gx, st);
+static hipError_t launch_pf_ts(const GemmP& p, int tg, int gx, int nbw, int merged, hipStream_t st) {
+    if (nbw == 1) return launch_pf_t<EPI, TS, 1>(p, tg, gx, merged, st);
+    if (nbw == 2) return launch_pf_t<EPI, TS, 2>(p, tg, gx, merged, st);
     if constexpr (TS <= 4) {   // 7 tile slots x 4 token blocks would not fit the register file
-        if (nbw == 4) return launch_pf_t<EPI, TS, 4>(p, tg, gx, st);
+        if (nbw == 4) return launch_pf_t<EPI, TS, 4>(p, tg, gx, merged, st);
     }
     return hipErrorInvalidValue;
 }
@@ -352,29 +353,32 @@ static hipError_t launch_pf(const GemmP& p_rows, bf16_t* xp, int n_cu, hipStream
         p.x_packed = 1;
     }
     const int n_tiles16 = p.out_rows / 16;
-    int tg = 1, ts = 4;
+    int tg = 1, ts = 4, merged = 0;
     if (p.n_groups != n_tiles16) {
-        // one row group per CU: 3 tiles per group - one group per workgroup; 1, 2 or 4 - four tile slots
+        // one row group per CU: 3 tiles per group - one group per workgroup; 1, 2 or 4 - four tile slots; groups of a
+        // whole tile and a tail of 4 rows (plain and residual epilogues) - two groups per workgroup, their tails in one slot
         const int units = p.out_rows / 4, max_units = (units + p.n_groups - 1) / p.n_groups;
         tg = (max_units * 4 + 15) / 16;
         if (tg > GRP_MAX_TILES) return hipErrorInvalidValue;
         ts = tg == 3 ? 3 : 4;
+        if ((EPI == EPI_PLAIN || EPI == EPI_RESID) && max_units == 5 && g_pf_merge != 0) { merged = 1; ts = 3; }
     } else {
         // one tile per group: 7 tiles per workgroup when there are very many (gate/up: 3584 = 2 x 256 x 7 at the 70B shape)
         ts = g_pf_ts ? g_pf_ts : (EPI == EPI_SWIGLU && n_tiles16 >= 4 * n_cu ? 7 : 4);
         if (ts != 4 && (ts != 7 || EPI != EPI_SWIGLU)) return hipErrorInvalidValue;
     }
-    const int gx = (p.n_groups + ts / tg - 1) / (ts / tg);
+    const int per_wg = merged ? ts - 1 : ts / tg;     // row groups of a workgroup
+    const int gx = (p.n_groups + per_wg - 1) / per_wg;
     // tokens per wave: as many as the block has, fewer while the grid would leave CUs without a workgroup
     int nbw = p.M <= 128 ? 1 : (p.M <= 256 ? 2 : 4);
     if (ts == 7) nbw = std::min(nbw, 2);
     while (nbw > 1 && gx * ((p.M + 128 * nbw - 1) / (128 * nbw)) < n_cu) nbw >>= 1;
     if (g_pf_nbw) nbw = std::min(g_pf_nbw, ts == 7 ? 2 : 4);
-    if (ts == 3) return launch_pf_ts<EPI, 3>(p, tg, gx, nbw, st);
+    if (ts == 3) return launch_pf_ts<EPI, 3>(p, tg, gx, nbw, merged, st);
     if constexpr (EPI == EPI_SWIGLU) {
-        if (ts == 7) return launch_pf_ts<EPI, 7>(p, tg, gx, nbw, st);
+        if (ts == 7) return launch_pf_ts<EPI, 7>(p, tg, gx, nbw, 0, st);
     }
-    return launch_pf_ts<EPI, 4>(p, tg, gx, nbw, st);
+    return launch_pf_ts<EPI, 4>(p, tg, gx, nbw, 0, st);
 }
 
 template <int EPI>

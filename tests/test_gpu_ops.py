@@ -119,12 +119,12 @@ def test_gemm_tiled_weight_layout_equals_row_major(M, out, inn):
 
 
 @pytest.mark.parametrize("M", [17, 100, 256, 300, 512])
-@pytest.mark.parametrize("out,inn", [(1024, 512), (8192, 2048), (10240, 1024), (15360, 1024), (5120, 13824), (27648, 512)])
+@pytest.mark.parametrize("out,inn", [(1024, 512), (8192, 2048), (10240, 1024), (15360, 1024), (5120, 13824), (4608, 512), (27648, 512)])
 def test_prefill_gemm_on_tile_major_weights(M, out, inn):
     """Blocks of more than 16 rows on tile-major weights (the prefill GEMM: weight operands shared through LDS,
     the block's rows read in operand order).  On a 256-CU device the shapes give one tile per row group (1024,
-    27648), groups of 2 tiles (8192), 3 (10240: 40 rows), 4 (15360: 60 rows) and of 20 rows (5120: a whole tile
-    and a quarter); the row counts give 1, 2 and 4 token blocks per wave, idle waves, and a ragged last block."""
+    27648), groups of 2 tiles (8192), 3 (10240: 40 rows), 4 (15360: 60 rows), of 20 rows (5120: a whole tile
+    and a quarter, the quarters of two groups gathered in one tile slot) and of 20 and 16 rows mixed (4608); the row counts give 1, 2 and 4 token blocks per wave, idle waves, and a ragged last block."""
     require_gpu()
     pk = _pk()
     g = torch.Generator(device="cpu").manual_seed(out + inn + M)
@@ -148,6 +148,16 @@ def test_prefill_gemm_on_tile_major_weights(M, out, inn):
         finally:
             pk.set_tunable("pf_rows", 0)
         assert float((Y0 - Y).abs().max()) <= 2e-5 * float(Y.abs().max())
+    if out in (5120, 4608):
+        # a tile slot per tail instead of the gathered one: the same sums in the same order
+        Y0 = torch.empty(M, out, device="cuda")
+        try:
+            pk.set_tunable("pf_merge", 0)
+            pk.op_gemm(pk.pack_weight(W.cuda()), X.cuda(), Y0, pk.GEMM_MFMA, weight_layout=pk.WEIGHTS_TILED)
+            torch.cuda.synchronize()
+        finally:
+            pk.set_tunable("pf_merge", -1)
+        assert torch.equal(Y0, Y)
 
 
 def test_pack_weight_is_a_permutation_of_16_byte_pieces():
