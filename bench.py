@@ -217,7 +217,7 @@ def time_prefill(ctx, torch, prompt, shape, si, reps=3):
             "frac": tf / MFMA_BF16_PEAK_TFLOPS}
 
 
-def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperature, tiled, steps):
+def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperature, tiled, steps, ar_tokens=0):
     """A short untimed-by-the-headline generation run on given weights: tokens/s and per-pass figures."""
     max_seq = (n_prompt + max_new + k_cap + 2 + 63) // 64 * 64
     ctx = pk.EESD(w, max_seq=max_seq, temperature=temperature, seed=0, k_cap=k_cap, kv_page=64,
@@ -235,8 +235,32 @@ def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperatu
     passes["temperature"] = temperature
     if shape["dtype"] == "bf16":
         passes["prefill"] = time_prefill(ctx, torch, prompts[0], shape, si)
+    if ar_tokens:
+        passes["autoregressive"] = autoregressive(ctx, torch, prompts[0], ar_tokens, passes["tokens_per_s"])
     ctx.close()
     return passes
+
+
+def autoregressive(ctx, torch, prompt, n_tokens, eesd_tokens_per_s):
+    """Plain auto-regressive decoding with the target model on the same context (the baseline of the paper's speed-up
+    figures, Section 4.1): every token is one single-row target pass and one draw from its distribution - a round with
+    no draft, driven call by call (verify, accept, rollback).  The ratio to the speculative rate is this run's speed-up,
+    at the acceptance the synthetic draft happens to have (random weights: 15-22 %), not the paper's."""
+    ctx.prefill(prompt)
+    for _ in range(4):
+        ctx.verify(); a, _ = ctx.accept(); ctx.rollback(a)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_tokens):
+        ctx.verify()
+        a, _ = ctx.accept()
+        ctx.rollback(a)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    rate = n_tokens / dt
+    return {"tokens_per_s": rate, "ms_per_token": dt / n_tokens * 1e3, "tokens": n_tokens, "prefill": "not in the rate",
+            "eesd_over_autoregressive": eesd_tokens_per_s / rate,
+            "note": "EESD rate: whole generations incl. prefill, acceptance of the synthetic draft"}
 
 
 def progress(msg):
@@ -359,6 +383,9 @@ def main():
     passes["weight_init_s"] = t_weights
     if bf16:
         passes["prefill"] = time_prefill(ctx, torch, prompts[0], shape, si)
+    if not args.headline_only and args.tree_width < 2 and args.controller == "beta":
+        passes["autoregressive"] = autoregressive(ctx, torch, prompts[0], 64, args.steps * max_new / dt)
+        progress("auto-regressive baseline timed")
     N, L = shape["n_draft_layers"], shape["n_layers"]
     esz = 2 if bf16 else 4
     kernel_bytes = 2 * shape["d_ff"] * shape["d_model"] * esz          # weights of one gate/up product
@@ -418,7 +445,7 @@ def main():
         shape13 = getattr(si, key13)
         w13 = pk.pack_weights(si.make_weights(shape13, seed=seed13, device="cuda"))
         torch.cuda.synchronize()
-        p13 = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 1.0, True, 4)
+        p13 = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 1.0, True, 4, ar_tokens=128)
         p13["workload"] = f"full EESD generation, {shape13['name']} (L={shape13['n_layers']}, N={shape13['n_draft_layers']}), prompt {np13}, {new13} new tokens, K cap {cap13}, temperature 1"
         p13["pass_frac"] = {"draft": p13["draft_step_GBps"] / HBM_PEAK_GBS, "verify": p13["verify_GBps"] / HBM_PEAK_GBS}
         out["passes_13b"] = p13
