@@ -417,6 +417,32 @@ def test_greedy_speculative_equals_greedy_autoregressive_on_gpu():
     assert spec == ar == o.ar_generate(prompt, 48)
 
 
+def test_sampled_rounds_without_drafts_are_autoregressive_sampling():
+    """Temperature 1, rounds with no draft (verify one row, accept, rollback): token t is the inverse-CDF draw from the
+    target's distribution with the resample uniform of round t - the oracle's plain auto-regressive sampler fed the same
+    uniforms gives the same text, compared up to the first draw that sits within the tolerance of a threshold."""
+    require_gpu()
+    from gpu_common import sample_margin
+    shape = si.TINY
+    seed, n = 17, 40
+    o, g = make_pair(shape, 11, 160, 1.0, k_cap=5, seed=seed)
+    prompt = si.make_prompt(20, shape["vocab"], 5)
+    us = [orc.uniform(seed, orc.STREAM_RESAMPLE, t) for t in range(n)]
+    want = o.ar_generate(prompt, n, uniforms=us)
+    got = [g.prefill(prompt)]
+    while len(got) < n:
+        g.verify()
+        a, y = g.accept()
+        assert a == 0
+        g.rollback(a)
+        got.append(y)
+    ref = orc.OracleEESD(o.w, 160, 1.0)
+    logits = ref.target_forward(list(prompt) + want[:-1], 0)[len(prompt) - 1:]
+    safe = next((t for t in range(n) if sample_margin(orc.softmax(logits[t].astype(np.float64)).astype(np.float32), us[t]) < 2e-5), n)
+    assert safe >= 10
+    assert got[:safe] == want[:safe]
+
+
 def test_rollback_equals_never_drafted_and_pages_return():
     require_gpu()
     shape = si.TINY
