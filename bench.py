@@ -418,6 +418,8 @@ def main():
                      "pass_frac": {"draft": (passes["draft_step_GBps"] or 0.0) / HBM_PEAK_GBS, "verify": (passes["verify_GBps"] or 0.0) / HBM_PEAK_GBS}},
         "passes": passes,
     }
+    if bf16:
+        out["roofline"]["prefill_frac_of_mfma_peak"] = passes["prefill"]["frac"]    # the one MFMA-bound part, against 2.5 PFLOP/s
     if args.latency_sweep and not extras:
         ks = [k for k in (0, 1, 2, 3, 5, 7, 10, 15) if k <= k_cap]
         out["latency_vs_K"] = latency_sweep(ctx, torch, sweep_tokens, ks, shape, si)
@@ -438,6 +440,19 @@ def main():
         out["cpu_baseline"] = cpu_baseline(cpu_w, shape, args.temperature, mean_k, mean_commit, si)
         progress("oracle timed on the host")
     if extras:
+        # the regime the method is made for - a draft that often agrees with the target: the same shape with a synthetic
+        # early-exit layer and head correlated with the target's (gamma 0.1), greedy decoding, and plain auto-regressive
+        # decoding on the same weights; the acceptance is a property of that synthetic pair, not of a trained model
+        del w
+        torch.cuda.empty_cache()
+        w = si.make_weights(shape, seed=wseed, device="cuda", correlated_draft=0.1)
+        if tiled:
+            w = pk.pack_weights(w)
+        torch.cuda.synchronize()
+        pc = side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, 0.0, tiled, 2, ar_tokens=64)
+        pc["workload"] = f"full EESD generation, {shape['name']}, early-exit layer and head correlated with the target (gamma 0.1), greedy, prompt {n_prompt}, {max_new} new tokens, K cap {k_cap}"
+        out["passes_correlated_draft_T0"] = pc
+        progress("correlated-draft generations done")
         # the 13B shape: the 70B weights go first
         del w
         torch.cuda.empty_cache()
@@ -449,6 +464,7 @@ def main():
         p13["workload"] = f"full EESD generation, {shape13['name']} (L={shape13['n_layers']}, N={shape13['n_draft_layers']}), prompt {np13}, {new13} new tokens, K cap {cap13}, temperature 1"
         p13["pass_frac"] = {"draft": p13["draft_step_GBps"] / HBM_PEAK_GBS, "verify": p13["verify_GBps"] / HBM_PEAK_GBS}
         out["passes_13b"] = p13
+        out["roofline"]["pass_frac_13b"] = p13["pass_frac"]          # the second shape the 70 % target names
         progress("13B-shape generations done")
         out["passes_13b_T0"] = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 0.0, True, 2)
         progress("13B-shape greedy generations done")
@@ -458,6 +474,7 @@ def main():
         pl["workload"] = f"full EESD generation, {shape13['name']}, prompt {npl}, {newl} new tokens, K cap {capl}, temperature 1"
         pl["pass_frac"] = {"draft": pl["draft_step_GBps"] / HBM_PEAK_GBS, "verify": pl["verify_GBps"] / HBM_PEAK_GBS}
         out["passes_13b_long"] = pl
+        out["roofline"]["pass_frac_13b_long_context"] = pl["pass_frac"]
         progress("13B-shape long-context generations done")
     print(json.dumps(out))
 
