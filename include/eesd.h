@@ -281,7 +281,8 @@ enum {
     EESD_READ_TREE_TOKENS = 8,   /* tree mode: the tokens of the block's 1 + K * tree_width rows as int32 */
     EESD_READ_CALI_STATE = 9,    /* three doubles: theta_hat, the observations behind it, verifications n */
     EESD_READ_VERIFY_PROBS = 10, /* index = verify row i: vocab floats, the probability row the last eesd_accept judged draft i on
-                                    (sampling mode; rows 0..a only: the accept kernel stops at the first rejection) */
+                                    (sampling mode; rows 0..a: the one-workgroup accept kernel stops at the first rejection, the kernels that take all
+                                    rows at once - "smp_spread" under eesd_set_tunable - fill the rows past a as well) */
     EESD_READ_LAUNCH_COUNTS = 11 /* 20 int32: weight-streaming product launches since eesd_create, [kernel][epilogue] with kernel
                                     0 = VALU family, 1 = one workgroup per 16-row tile, 2 = one workgroup per row group,
                                     3 = tiles sharing the activations through LDS, 4 = prefill GEMM on tile-major weights;
