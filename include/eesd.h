@@ -229,7 +229,8 @@ int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t
 /* Where the operand-order layouts keep an element, as the kernels compute it (for tests of the layouts; -1 on bad
  * arguments).  what = 0: key of slot a (position inside its KV page), channel b, head_dim n -> element offset inside one
  * KV head's block of the page; 1: the same for a value; 2: activation row a, column b of a prefill block with 32 n
- * columns -> element offset inside the block's buffer. */
+ * columns -> element offset inside the block's buffer; 3 / 4: first row / number of rows of row group a of a tile-major
+ * matrix of b rows (a multiple of 16) on a device of n compute units; 5: the number of row groups of that matrix. */
 int64_t eesd_host_layout_offset(int32_t what, int32_t a, int32_t b, int32_t n);
 
 /* ---- Thompson sampling with calibration (Section 3.3 Eq. 5-8, Algorithm 3) ------------ */

@@ -994,6 +994,14 @@ extern "C" int64_t eesd_host_layout_offset(int32_t what, int32_t a, int32_t b, i
     if (what == 0) return n % 32 ? -1 : (int64_t)kv_tiled_k(a, b, n);       // key slot a (inside its page), channel b, head_dim n
     if (what == 1) return n % 32 ? -1 : (int64_t)kv_tiled_v(a, b, n);       // value slot a, channel b, head_dim n
     if (what == 2) return (int64_t)act_packed_offset(a, b, n);               // activation row a, column b, n = columns / 32
+    if (what == 3 || what == 4) {                                             // row group a of a matrix of b rows on n CUs: first row / rows
+        if (b < 16 || b % 16) return -1;
+        const int groups = pack_n_groups(b, n);
+        if (a >= groups) return -1;
+        const GroupGeom gg = group_geom(a, groups, b);
+        return what == 3 ? gg.row0 : gg.rows;
+    }
+    if (what == 5) return (b < 16 || b % 16) ? -1 : pack_n_groups(b, n);     // row groups of a matrix of b rows on n CUs
     return -1;
 }
 extern "C" int eesd_host_ts_update(double* alpha, double* beta, int32_t n_accepted, int32_t n_drafted, int32_t reading) {

@@ -108,3 +108,23 @@ def test_operand_order_layouts_are_permutations_with_the_mfma_lane_order():
         for c in range(32 * steps):
             assert act[m, c] == ((((m // 16) * steps + c // 32) * 64) + ((c % 32) // 8) * 16 + m % 16) * 8 + c % 8
     assert pk.host_layout_offset(0, 0, 0, 48) == -1 and pk.host_layout_offset(7, 0, 0, 64) == -1
+
+
+def test_row_groups_partition_a_matrix_in_units_of_four_rows():
+    """Tile-major weights: matrices with more tiles than CUs but fewer than four per CU are dealt to one row group per
+    CU in units of 4 rows - consecutive, covering every row once, the first groups one unit larger; the others keep
+    one 16-row tile per group."""
+    import paper_2406_03853_amd as pk
+    n_cu = 256
+    for rows, want_groups in ((5120, 256), (8192, 256), (10240, 256), (15360, 256), (4608, 256), (4096, 256), (1024, 64), (27648, 1728), (32000, 2000)):
+        groups = pk.host_layout_offset(5, 0, rows, n_cu)
+        assert groups == want_groups
+        geo = [(pk.host_layout_offset(3, g, rows, n_cu), pk.host_layout_offset(4, g, rows, n_cu)) for g in range(groups)]
+        assert geo[0][0] == 0 and geo[-1][0] + geo[-1][1] == rows
+        assert all(geo[g][0] + geo[g][1] == geo[g + 1][0] for g in range(groups - 1))
+        sizes = [r for _, r in geo]
+        assert all(r % 4 == 0 and r > 0 for r in sizes) and max(sizes) - min(sizes) in (0, 4)
+        assert sizes == sorted(sizes, reverse=True)
+        if groups == rows // 16:
+            assert set(sizes) == {16}
+    assert pk.host_layout_offset(3, 256, 5120, n_cu) == -1 and pk.host_layout_offset(5, 0, 5000, n_cu) == -1
