@@ -217,13 +217,17 @@ def time_prefill(ctx, torch, prompt, shape, si, reps=3):
             "frac": tf / MFMA_BF16_PEAK_TFLOPS}
 
 
-def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperature, tiled, steps, ar_tokens=0):
+def side_generation(pk, si, torch, w, shape, n_prompt, max_new, k_cap, temperature, tiled, steps, ar_tokens=0, warmup_s=0.0):
     """A short untimed-by-the-headline generation run on given weights: tokens/s and per-pass figures."""
     max_seq = (n_prompt + max_new + k_cap + 2 + 63) // 64 * 64
     ctx = pk.EESD(w, max_seq=max_seq, temperature=temperature, seed=0, k_cap=k_cap, kv_page=64,
                   weight_layout=pk.WEIGHTS_TILED if tiled else pk.WEIGHTS_ROW_MAJOR)
     prompts = [si.make_prompt(n_prompt, shape["vocab"], 100 + i) for i in range(steps)]
+    # untimed warm-up: one generation, or as many as fill warmup_s seconds (for the seconds after a large free, see the caller)
+    t_warm = time.perf_counter()
     ctx.generate(prompts[-1], max_new)
+    while time.perf_counter() - t_warm < warmup_s:
+        ctx.generate(prompts[-1], max_new)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     stats = [ctx.generate(prompts[i], max_new)[1] for i in range(steps)]
@@ -460,7 +464,10 @@ def main():
         shape13 = getattr(si, key13)
         w13 = pk.pack_weights(si.make_weights(shape13, seed=seed13, device="cuda"))
         torch.cuda.synchronize()
-        p13 = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 1.0, True, 4, ar_tokens=128)
+        # (For about 5 s after the 137 GB of 70B-shape weights have been given back, every pass on the device runs 2 % slower
+        # - 13B-shape draft step 0.766 against 0.750 ms - whatever memory it uses, and then returns to its rate while
+        # the work goes on; the warm-up generations cover that time.)
+        p13 = side_generation(pk, si, torch, w13, shape13, np13, new13, cap13, 1.0, True, 4, ar_tokens=128, warmup_s=8.0)
         p13["workload"] = f"full EESD generation, {shape13['name']} (L={shape13['n_layers']}, N={shape13['n_draft_layers']}), prompt {np13}, {new13} new tokens, K cap {cap13}, temperature 1"
         p13["pass_frac"] = {"draft": p13["draft_step_GBps"] / HBM_PEAK_GBS, "verify": p13["verify_GBps"] / HBM_PEAK_GBS}
         out["passes_13b"] = p13
